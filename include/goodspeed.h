@@ -1,0 +1,200 @@
+/*
+ * goodspeed.h - C ABI of the verification-server hot path of GoodSpeed
+ * (adaptive speculative decoding with N draft servers and one verifier).
+ *
+ * One round, verifier side (paper: Algorithm 1, verification-server steps;
+ * Figure 1 steps 3-5):
+ *   gs_verify_batch   target-decoder forward over the ragged speculative blocks
+ *                     of all servers, then rejection-verification
+ *   gs_accept_reject  rejection-verification alone, on given target logits
+ *   gs_schedule_gamma estimator updates and the per-round scheduling problem
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers ordinary host
+ *     memory.  Every buffer is owned by the caller; the library allocates no
+ *     device memory and keeps no pointer after a call returns, except that a
+ *     gs_ctx keeps the weight pointers given to gs_create.
+ *   - GPU entry points only enqueue work on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream); outputs are valid once the caller has
+ *     synchronised that stream.  Two calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Every entry point returns a gs_status; nothing throws or aborts.  All
+ *     argument checks happen on the host before the first launch, so a failed
+ *     call has launched nothing.  gs_last_error() gives the message of the last
+ *     failure on the calling thread.
+ *   - Server i drafts gamma[i] tokens (the paper's S_i(t)).  Its block has
+ *     T_i = gamma[i] + 1 target rows: the pending token (the correction/bonus
+ *     token of the previous round, not yet in the KV cache) followed by the
+ *     drafts.  Row j (0-based) of a block yields p_{j+1}, so the block yields
+ *     p_1 .. p_{gamma+1} as the rejection rule needs (paper Section II-A-2).
+ *     Rows of all servers are concatenated in server order: R = sum T_i target
+ *     rows, G = sum gamma[i] draft rows.  cu_rows[i] = first target row of
+ *     server i, cu_rows[N] = R; the first draft row of server i is cu_rows[i] - i.
+ */
+#ifndef GOODSPEED_H
+#define GOODSPEED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GS_OK = 0,
+  GS_EINVAL = -1,       /* null pointer, negative size, inconsistent descriptor */
+  GS_ESHAPE = -2,       /* model shape the kernels do not support              */
+  GS_ECAPACITY = -3,    /* workspace or KV pages too small                     */
+  GS_EDEVICE = -4,      /* a HIP call failed                                   */
+  GS_EUNSUPPORTED = -5
+} gs_status;
+
+enum { GS_F32 = 0, GS_BF16 = 1 };
+
+/* Message of the last error on this thread (static storage, never NULL). */
+const char* gs_last_error(void);
+
+/* ------------------------------------------------------------------------- */
+/* Rejection-verification (paper Section II-A-2; statistic: the sum inside the  */
+/* acceptance-rate update of Section III-C).                                    */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+  int* accepted_len;   /* dev [N]  m_i in [0, gamma_i]: drafts kept before the first rejection      */
+  int* next_token;     /* dev [N]  s'_i: drawn from normalised max(0, p_{m+1} - q_{m+1}) if          */
+                       /*          m_i < gamma_i, else from p_{gamma+1}                              */
+  float* accept_stat;  /* dev [N]  (1/gamma_i) sum over ALL gamma_i positions of min(1, p/q);        */
+                       /*          0 when gamma_i = 0                                                */
+  float* ratio;        /* dev [G]  p_j(s_j)/q_j(s_j) per draft row (+inf when q = 0); may be NULL    */
+} gs_accept_out;
+
+/* Bytes of device workspace gs_accept_reject needs for these sizes. */
+size_t gs_accept_workspace_bytes(int n_servers, int n_rows, int vocab);
+
+/*
+ * Accept/reject + resample for N servers.
+ *   gamma_host    host [N]      draft lengths, each >= 0
+ *   cu_rows       dev  [N+1]    prefix offsets of T_i = gamma_i + 1 (must match gamma_host)
+ *   target_logits dev  [R, V]   fp32 row-major; p = softmax(row)
+ *   q_probs       dev  [G, V]   fp32 draft probabilities
+ *   draft_tokens  dev  [G]      token ids in [0, V)
+ *   u_accept      dev  [G]      uniforms in [0,1): token j accepted iff u <= p/q
+ *   u_resample    dev  [N]      uniforms in [0,1) for the inverse-CDF draw of s'
+ * The draw returns the smallest token whose running sum of weights exceeds
+ * u * (total weight), tokens in index order; a zero-weight token is never
+ * returned.  If max(0, p - q) has no mass the draw falls back to p.
+ * Errors: GS_EINVAL (null pointers, N <= 0, vocab <= 0, gamma < 0),
+ * GS_ECAPACITY (workspace too small), GS_EDEVICE.
+ */
+gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                           const float* target_logits, const float* q_probs,
+                           const int* draft_tokens, const float* u_accept, const float* u_resample,
+                           const gs_accept_out* out, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/* ------------------------------------------------------------------------- */
+/* Estimators and GoodSpeed-sched (paper Section III-C: the alpha-hat and X      */
+/* smoothing equations and the scheduling problem; Algorithm 1 orders the       */
+/* updates before the solve).  Pure host code.                                  */
+/* ------------------------------------------------------------------------- */
+
+/*
+ *   accepted_len host [N]  m_i of the round just verified
+ *   accept_stat  host [N]  mean min(1, p/q) of that round (ignored where gamma_prev = 0)
+ *   gamma_prev   host [N]  draft lengths of that round
+ *   alpha_hat    host [N]  in/out: (1-eta) alpha_hat + eta * accept_stat
+ *   x_smooth     host [N]  in/out: (1-beta) X + beta * (m_i + 1)
+ *   gamma_next   host [N]  out: maximiser of sum_i (1/X_i) (1 - a_i^(S_i+1))/(1 - a_i)
+ *                          subject to sum S_i <= capacity, gamma_min <= S_i <= gamma_max
+ * alpha_hat is clamped to [1e-6, 1-1e-6] inside the solve only.  gamma_max < 0
+ * means unbounded.  Ties go to the lowest server index.
+ * Errors: GS_EINVAL (null, n <= 0, eta/beta outside [0,1], X <= 0 after update,
+ * capacity < n * gamma_min, gamma_min < 0).
+ */
+gs_status gs_schedule_gamma(int n, const int* accepted_len, const float* accept_stat,
+                            const int* gamma_prev, double* alpha_hat, double* x_smooth,
+                            double eta, double beta, int capacity, int gamma_min, int gamma_max,
+                            int* gamma_next);
+
+/* ------------------------------------------------------------------------- */
+/* Batched verification step: decoder forward + rejection-verification          */
+/* (paper Section II-A-1 for p = softmax(W h); Section II-A-2 for verification;  */
+/* Figure 1 steps 3 and 4).  The decoder is a Llama-style stack: pre-norm        */
+/* RMSNorm, rotary embedding (pairs (i, i + hd/2), inverse frequency             */
+/* theta^(-2i/hd)), grouped-query causal attention, SwiGLU, no biases.           */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+  int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_theta, rms_eps;
+  int dtype;            /* GS_F32 or GS_BF16: storage type of weights, KV pages and GEMM operands */
+} gs_model_desc;
+
+/* All matrices are row-major [out_features, in_features] in the model dtype. */
+typedef struct {
+  const void* embed;          /* dev [V, d]                                              */
+  const void* lm_head;        /* dev [V, d]                                              */
+  const float* final_norm;    /* dev [d] fp32                                            */
+  const void* const* wqkv;    /* host [n_layers] of dev [(H + 2 H_kv) hd, d]: Q heads, K heads, V heads */
+  const void* const* wo;      /* host [n_layers] of dev [d, H hd]                        */
+  const void* const* wgu;     /* host [n_layers] of dev [2 F, d]: gate rows, then up rows */
+  const void* const* wd;      /* host [n_layers] of dev [d, F]                           */
+  const float* const* norm1;  /* host [n_layers] of dev [d] fp32 (attention pre-norm)    */
+  const float* const* norm2;  /* host [n_layers] of dev [d] fp32 (FFN pre-norm)          */
+} gs_weights;
+
+/* Paged KV cache, model dtype, layout [n_layers][n_pages][H_kv][page_size][hd]; K is stored rotated. */
+typedef struct {
+  void* k_pages;
+  void* v_pages;
+  int page_size;
+  int n_pages;
+} gs_kv_cache;
+
+typedef struct {
+  int n_servers;
+  const int* gamma_host;     /* host [N]                                                       */
+  const int* ctx_len_host;   /* host [N]  tokens already cached per server                     */
+  const int* cu_rows;        /* dev  [N+1] (matches gamma_host)                                */
+  const int* ctx_len;        /* dev  [N]   (matches ctx_len_host)                              */
+  const int* tokens;         /* dev  [R]   pending token then drafts, per server               */
+  const int* block_table;    /* dev  [N, max_blocks] physical page of each logical block       */
+  int max_blocks;
+  const float* q_probs;      /* dev  [G, V]                                                    */
+  const float* u_accept;     /* dev  [G]                                                       */
+  const float* u_resample;   /* dev  [N]                                                       */
+} gs_batch;
+
+typedef struct gs_ctx gs_ctx;
+
+/* Validates the shape and copies the descriptor and the per-layer pointer tables.
+ * Supported: head_dim in {64, 128}; n_heads a multiple of n_kv_heads with group <= 8;
+ * d_model, d_ffn and every projection width multiples of 64.  Errors: GS_EINVAL, GS_ESHAPE. */
+gs_status gs_create(const gs_model_desc* desc, const gs_weights* weights, gs_ctx** out);
+gs_status gs_destroy(gs_ctx* ctx);
+
+/* Device workspace gs_verify_batch needs for batches of at most max_rows target rows,
+ * max_servers servers and max_ctx tokens of context (cached + block) per server. */
+size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx);
+
+/*
+ * One verification step.  Runs the decoder over all R rows at positions
+ * ctx_len[i] + j, WRITES the block's K/V rows into the cache pages at those
+ * positions (the caller advances ctx_len by m_i + 1 afterwards; rows beyond
+ * that are dead and overwritten next round), then runs gs_accept_reject on the
+ * resulting logits.
+ *   logits_out  dev [R, V] fp32, or NULL to keep the logits in the workspace only
+ *   out->*      as for gs_accept_reject; if batch->q_probs is NULL the step stops
+ *               after the logits (prefill use) and `out` may be NULL.
+ * Errors: GS_EINVAL, GS_ECAPACITY (workspace; a block table too short for
+ * ctx_len + T_i tokens), GS_EDEVICE.
+ */
+gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* batch,
+                          const gs_accept_out* out, float* logits_out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOODSPEED_H */

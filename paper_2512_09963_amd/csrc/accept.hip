@@ -1,0 +1,472 @@
+// Rejection-verification on the GPU: vocabulary softmax statistics, the accept
+// test, and the residual / bonus draw (paper Section II-A-2; the per-server
+// statistic is the sum inside the acceptance-rate update of Section III-C).
+//
+// Four launches on one stream, no host synchronisation:
+//   row_stats      every target row is read once; each workgroup reduces one chunk of
+//                  one row to an online-softmax pair (max, sum exp(l - max))
+//   decide         one wavefront per server: merges the chunk pairs of its rows, gathers
+//                  p_j(s_j) and q_j(s_j), takes the accept decisions, finds m and the statistic
+//   residual_tiles one workgroup per 2048-token tile of the single row each server draws
+//                  from: sum of max(0, p - q) (or of p for the bonus draw)
+//   pick_token     one workgroup per server: locates the tile, then the token, whose running
+//                  sum first exceeds u * total
+// Bandwidth-bound: row_stats streams 4*V bytes per target row with 16-byte loads and keeps
+// four loads per lane in flight; everything else touches O(N*V) bytes.
+#include "common.h"
+#include <cmath>
+
+namespace gs {
+namespace {
+
+constexpr int kStatsThreads = 256;
+constexpr int kTileThreads = 256;
+constexpr int kTileElems = 2048;              // 256 lanes x 8 tokens
+constexpr int kMaxChunks = 64;
+
+struct Decision {    // per server, written by decide, read by the draw kernels
+  int row;           // target row the extra token is drawn from (first row + m)
+  int q_row;         // draft row whose q is subtracted, or -1 for the bonus draw from p
+  float row_max;     // softmax statistics of that row
+  float inv_z;
+};
+
+__device__ __forceinline__ void merge_pair(float& m, float& s, float m2, float s2) {
+  float M = fmaxf(m, m2);
+  float a = (m == -INFINITY) ? 0.f : s * __expf(m - M);
+  float b = (m2 == -INFINITY) ? 0.f : s2 * __expf(m2 - M);
+  m = M;
+  s = a + b;
+}
+
+__device__ __forceinline__ float max4(const float4& v) { return fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)); }
+
+// ---------------------------------------------------------------------------------------
+// row_stats: grid (chunks, rows).  VEC: rows are 16-byte aligned and V % 4 == 0.
+// ---------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* __restrict__ logits, int vocab,
+                                                                   int chunk_len, float2* __restrict__ partial) {
+  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
+  const int begin = chunk * chunk_len;
+  const int end = min(vocab, begin + chunk_len);
+  const float* base = logits + (size_t)row * vocab;
+  float m = -INFINITY, s = 0.f;
+  const float4 neg = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+
+  if (VEC) {
+    const float4* p = reinterpret_cast<const float4*>(base + begin);
+    const int n4 = (end - begin) >> 2;
+    for (int i = threadIdx.x; i < n4; i += 4 * kStatsThreads) {
+      float4 v0 = p[i];
+      float4 v1 = (i + kStatsThreads < n4) ? p[i + kStatsThreads] : neg;
+      float4 v2 = (i + 2 * kStatsThreads < n4) ? p[i + 2 * kStatsThreads] : neg;
+      float4 v3 = (i + 3 * kStatsThreads < n4) ? p[i + 3 * kStatsThreads] : neg;
+      float bm = fmaxf(fmaxf(max4(v0), max4(v1)), fmaxf(max4(v2), max4(v3)));
+      if (bm > m) {
+        s *= __expf(m - bm);     // m = -inf gives exp(-inf) = 0 and s is 0 anyway
+        m = bm;
+      }
+      const float mm = (m == -INFINITY) ? 0.f : m;   // a lane that has seen only -inf adds exp(-inf) = 0
+      float a0 = __expf(v0.x - mm) + __expf(v0.y - mm) + __expf(v0.z - mm) + __expf(v0.w - mm);
+      float a1 = __expf(v1.x - mm) + __expf(v1.y - mm) + __expf(v1.z - mm) + __expf(v1.w - mm);
+      float a2 = __expf(v2.x - mm) + __expf(v2.y - mm) + __expf(v2.z - mm) + __expf(v2.w - mm);
+      float a3 = __expf(v3.x - mm) + __expf(v3.y - mm) + __expf(v3.z - mm) + __expf(v3.w - mm);
+      s += (a0 + a1) + (a2 + a3);
+    }
+  } else {
+    for (int i = begin + threadIdx.x; i < end; i += kStatsThreads) {
+      float v = base[i];
+      if (v > m) {
+        s *= __expf(m - v);
+        m = v;
+      }
+      s += __expf(v - ((m == -INFINITY) ? 0.f : m));
+    }
+  }
+
+  // wavefront then workgroup merge (fixed order: deterministic)
+  for (int off = 32; off > 0; off >>= 1) {
+    float m2 = __shfl_down(m, off);
+    float s2 = __shfl_down(s, off);
+    merge_pair(m, s, m2, s2);
+  }
+  __shared__ float sm[kStatsThreads / 64], ss[kStatsThreads / 64];
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    sm[wave] = m;
+    ss[wave] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < kStatsThreads / 64; ++w) merge_pair(m, s, sm[w], ss[w]);
+    partial[(size_t)row * n_chunks + chunk] = make_float2(m, s);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// decide: one 64-lane workgroup per server.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void decide_kernel(const int* __restrict__ cu_rows, int vocab, int n_chunks,
+                                                     const float2* __restrict__ partial,
+                                                     const float* __restrict__ logits, const float* __restrict__ q_probs,
+                                                     const int* __restrict__ draft_tokens,
+                                                     const float* __restrict__ u_accept, int* __restrict__ accepted_len,
+                                                     float* __restrict__ accept_stat, float* __restrict__ ratio_out,
+                                                     Decision* __restrict__ decision) {
+  const int srv = blockIdx.x;
+  const int row0 = cu_rows[srv];
+  const int gamma = cu_rows[srv + 1] - row0 - 1;
+  const int d0 = row0 - srv;
+  const int lane = threadIdx.x;
+
+  int first_reject = gamma;    // smallest rejected draft index seen by this lane
+  float stat = 0.f;
+  for (int j = lane; j < gamma; j += 64) {
+    const int row = row0 + j;
+    float m = -INFINITY, s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+      float2 ps = partial[(size_t)row * n_chunks + c];
+      merge_pair(m, s, ps.x, ps.y);
+    }
+    const int tok = draft_tokens[d0 + j];
+    const float p = expf(logits[(size_t)row * vocab + tok] - m) / s;
+    const float q = q_probs[(size_t)(d0 + j) * vocab + tok];
+    const float ratio = (q == 0.f) ? INFINITY : p / q;
+    if (ratio_out) ratio_out[d0 + j] = ratio;
+    stat += fminf(1.f, ratio);
+    if (u_accept[d0 + j] > ratio) first_reject = min(first_reject, j);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    first_reject = min(first_reject, __shfl_down(first_reject, off));
+    stat += __shfl_down(stat, off);
+  }
+  first_reject = __shfl(first_reject, 0);
+  if (lane == 0) {
+    const int m_acc = first_reject;
+    accepted_len[srv] = m_acc;
+    accept_stat[srv] = gamma > 0 ? stat / (float)gamma : 0.f;
+    const int row = row0 + m_acc;
+    float m = -INFINITY, s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+      float2 ps = partial[(size_t)row * n_chunks + c];
+      merge_pair(m, s, ps.x, ps.y);
+    }
+    Decision d;
+    d.row = row;
+    d.q_row = (m_acc < gamma) ? d0 + m_acc : -1;
+    d.row_max = m;
+    d.inv_z = 1.f / s;
+    decision[srv] = d;
+  }
+}
+
+// Weight of token t in the draw: max(0, p - q) or p.
+__device__ __forceinline__ float draw_weight(float logit, float q, float row_max, float inv_z, bool residual) {
+  float p = expf(logit - row_max) * inv_z;
+  return residual ? fmaxf(0.f, p - q) : p;
+}
+
+// Loads this lane's 8 consecutive weights of a tile; tokens >= vocab weigh 0.
+template <bool VEC>
+__device__ __forceinline__ void load_weights8(const float* __restrict__ lrow, const float* __restrict__ qrow, int t0,
+                                              int vocab, float row_max, float inv_z, bool residual, float w[8]) {
+  if (VEC && t0 + 8 <= vocab) {
+    const float4 l0 = *reinterpret_cast<const float4*>(lrow + t0);
+    const float4 l1 = *reinterpret_cast<const float4*>(lrow + t0 + 4);
+    float4 q0 = make_float4(0, 0, 0, 0), q1 = q0;
+    if (residual) {
+      q0 = *reinterpret_cast<const float4*>(qrow + t0);
+      q1 = *reinterpret_cast<const float4*>(qrow + t0 + 4);
+    }
+    w[0] = draw_weight(l0.x, q0.x, row_max, inv_z, residual);
+    w[1] = draw_weight(l0.y, q0.y, row_max, inv_z, residual);
+    w[2] = draw_weight(l0.z, q0.z, row_max, inv_z, residual);
+    w[3] = draw_weight(l0.w, q0.w, row_max, inv_z, residual);
+    w[4] = draw_weight(l1.x, q1.x, row_max, inv_z, residual);
+    w[5] = draw_weight(l1.y, q1.y, row_max, inv_z, residual);
+    w[6] = draw_weight(l1.z, q1.z, row_max, inv_z, residual);
+    w[7] = draw_weight(l1.w, q1.w, row_max, inv_z, residual);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = t0 + k;
+      w[k] = (t < vocab) ? draw_weight(lrow[t], residual ? qrow[t] : 0.f, row_max, inv_z, residual) : 0.f;
+    }
+  }
+}
+
+__device__ __forceinline__ float sum8(const float w[8]) {
+  return ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+}
+
+// ---------------------------------------------------------------------------------------
+// residual_tiles: grid (tiles, servers).  force_p: redo a server's tiles with weights p
+// (only used when its residual had no mass).
+// ---------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kTileThreads) void residual_tiles_kernel(const Decision* __restrict__ decision, int vocab,
+                                                                       const float* __restrict__ logits,
+                                                                       const float* __restrict__ q_probs,
+                                                                       double* __restrict__ tile_sums) {
+  const int tile = blockIdx.x, srv = blockIdx.y, n_tiles = gridDim.x;
+  const Decision d = decision[srv];
+  const bool residual = d.q_row >= 0;
+  const float* lrow = logits + (size_t)d.row * vocab;
+  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
+  float w[8];
+  load_weights8<VEC>(lrow, qrow, tile * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, residual, w);
+  double acc = (double)sum8(w);
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+  __shared__ double part[kTileThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = part[0];
+    for (int wv = 1; wv < kTileThreads / 64; ++wv) t += part[wv];
+    tile_sums[(size_t)srv * n_tiles + tile] = t;
+  }
+}
+
+// Workgroup-wide scan of one double per lane (256 lanes).  Returns the inclusive sum and sets
+// excl to the inclusive sum of the previous lane (0 for lane 0), bit-identical to what that
+// lane returns, so "first lane whose inclusive sum crosses a threshold" is unique.
+__device__ __forceinline__ double block_scan(double v, double* wave_tot /*[4] shared*/, double& excl) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int off = 1; off < 64; off <<= 1) {
+    double o = __shfl_up(v, off);
+    if (lane >= off) v += o;
+  }
+  double prev = __shfl_up(v, 1);
+  if (lane == 63) wave_tot[wave] = v;
+  __syncthreads();
+  double add = 0.0, add_prev = 0.0;
+  for (int wv = 0; wv < wave; ++wv) {
+    add_prev = add;
+    add += wave_tot[wv];
+  }
+  // previous lane of lane 0 is lane 63 of the wave before: its value is wave_tot[wave-1] + add_prev
+  excl = (lane == 0) ? (wave == 0 ? 0.0 : wave_tot[wave - 1] + add_prev) : prev + add;
+  __syncthreads();
+  return v + add;
+}
+
+// ---------------------------------------------------------------------------------------
+// pick_token: one workgroup per server.
+// ---------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision* __restrict__ decision, int vocab,
+                                                                   int n_tiles, const float* __restrict__ logits,
+                                                                   const float* __restrict__ q_probs,
+                                                                   const double* __restrict__ tile_sums,
+                                                                   const float* __restrict__ u_resample,
+                                                                   int* __restrict__ next_token) {
+  const int srv = blockIdx.x;
+  const Decision d = decision[srv];
+  bool residual = d.q_row >= 0;
+  const float* lrow = logits + (size_t)d.row * vocab;
+  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
+  __shared__ double wave_tot[kTileThreads / 64];
+  __shared__ double sh_prefix;
+  __shared__ int sh_tile, sh_found, sh_last_pos;
+  float w[8];
+
+  // total mass (sequential over the few tile sums, one lane: deterministic)
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int t = 0; t < n_tiles; ++t) tot += tile_sums[(size_t)srv * n_tiles + t];
+    sh_prefix = tot;
+  }
+  __syncthreads();
+  double total = sh_prefix;
+  __syncthreads();
+
+  const bool fallback = residual && !(total > 0.0);   // residual without mass: draw from p instead
+  if (fallback) {
+    residual = false;
+    // recompute the total of p tile by tile (rare path, one workgroup walks the row)
+    double tot = 0.0;
+    for (int t = 0; t < n_tiles; ++t) {
+      load_weights8<VEC>(lrow, nullptr, t * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, false, w);
+      double ex;
+      double incl = block_scan((double)sum8(w), wave_tot, ex);
+      if (threadIdx.x == kTileThreads - 1) sh_prefix = incl;
+      __syncthreads();
+      tot += sh_prefix;
+      __syncthreads();
+    }
+    total = tot;
+  }
+
+  const double target = (double)u_resample[srv] * total;
+  if (threadIdx.x == 0) {
+    sh_found = -1;
+    sh_last_pos = -1;
+    sh_tile = n_tiles - 1;
+    sh_prefix = 0.0;
+  }
+  __syncthreads();
+
+  if (!fallback) {
+    if (threadIdx.x == 0) {
+      double run = 0.0;
+      int t = 0;
+      for (; t < n_tiles; ++t) {
+        double nxt = run + tile_sums[(size_t)srv * n_tiles + t];
+        if (nxt > target) break;
+        run = nxt;
+      }
+      if (t == n_tiles) {          // rounding left no crossing: last tile with mass
+        t = n_tiles - 1;
+        while (t > 0 && !(tile_sums[(size_t)srv * n_tiles + t] > 0.0)) --t;
+        run = 0.0;
+        for (int k = 0; k < t; ++k) run += tile_sums[(size_t)srv * n_tiles + k];
+      }
+      sh_tile = t;
+      sh_prefix = run;
+    }
+    __syncthreads();
+  }
+
+  // Walk tiles: a single tile in the normal path, all tiles until found in the fallback path.
+  int tile = fallback ? 0 : sh_tile;
+  double prefix = fallback ? 0.0 : sh_prefix;
+  int last_pos_any = -1;
+  for (;;) {
+    const int t0 = tile * kTileElems + threadIdx.x * 8;
+    load_weights8<VEC>(lrow, qrow, t0, vocab, d.row_max, d.inv_z, residual, w);
+    double excl;
+    const double incl = block_scan((double)sum8(w), wave_tot, excl);
+    // exactly one lane sees the running sum cross the target inside its 8 tokens
+    if ((prefix + incl > target) && !(prefix + excl > target)) {
+      double run = prefix + excl;
+      int pick = -1, last = -1;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        run += (double)w[k];
+        if (w[k] > 0.f) {
+          last = t0 + k;
+          if (pick < 0 && run > target) pick = t0 + k;
+        }
+      }
+      sh_found = pick >= 0 ? pick : last;   // lane-local sum order may differ in the last bit
+    }
+    int lp = -1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (w[k] > 0.f) lp = t0 + k;
+    if (lp >= 0) atomicMax(&sh_last_pos, lp);
+    if (threadIdx.x == kTileThreads - 1) sh_prefix = prefix + incl;
+    __syncthreads();
+    const int found = sh_found;
+    prefix = sh_prefix;
+    last_pos_any = sh_last_pos;
+    __syncthreads();
+    if (found >= 0 || !fallback || tile == n_tiles - 1) {
+      if (threadIdx.x == 0) next_token[srv] = found >= 0 ? found : max(last_pos_any, 0);
+      break;
+    }
+    ++tile;
+  }
+}
+
+inline int pick_chunks(int n_rows, int vocab) {
+  int want = ceil_div(4096, n_rows > 0 ? n_rows : 1);
+  int cap = vocab / 4096 > 0 ? vocab / 4096 : 1;
+  int c = want < cap ? want : cap;
+  if (c < 1) c = 1;
+  if (c > kMaxChunks) c = kMaxChunks;
+  return c;
+}
+
+struct AcceptPlan {
+  int n_chunks, chunk_len, n_tiles;
+  size_t bytes;
+  float2* partial;
+  Decision* decision;
+  double* tile_sums;
+};
+
+AcceptPlan plan_accept(int n_servers, int n_rows, int vocab, void* workspace) {
+  AcceptPlan p;
+  p.n_chunks = pick_chunks(n_rows, vocab);
+  p.chunk_len = (ceil_div(vocab, p.n_chunks) + 3) / 4 * 4;
+  p.n_chunks = ceil_div(vocab, p.chunk_len);
+  p.n_tiles = ceil_div(vocab, kTileElems);
+  Carver c(workspace);
+  p.partial = c.take<float2>((size_t)n_rows * p.n_chunks);
+  p.decision = c.take<Decision>(n_servers);
+  p.tile_sums = c.take<double>((size_t)n_servers * p.n_tiles);
+  p.bytes = c.used();
+  return p;
+}
+
+}  // namespace
+
+// Enqueues the four kernels; arguments already validated.  n_rows = sum(gamma + 1).
+gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
+                        const float* q_probs, const int* draft_tokens, const float* u_accept,
+                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream) {
+  AcceptPlan p = plan_accept(n_servers, n_rows, vocab, workspace);
+  const bool vec = (vocab % 4 == 0) && (reinterpret_cast<uintptr_t>(target_logits) % 16 == 0) &&
+                   (q_probs == nullptr || reinterpret_cast<uintptr_t>(q_probs) % 16 == 0);
+  dim3 g1(p.n_chunks, n_rows);
+  if (vec)
+    row_stats_kernel<true><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.partial);
+  else
+    row_stats_kernel<false><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.partial);
+  GS_LAUNCH_CHECK("row_stats");
+  decide_kernel<<<n_servers, 64, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.partial, target_logits, q_probs,
+                                              draft_tokens, u_accept, out->accepted_len, out->accept_stat,
+                                              out->ratio, p.decision);
+  GS_LAUNCH_CHECK("decide");
+  dim3 g3(p.n_tiles, n_servers);
+  if (vec) {
+    residual_tiles_kernel<true><<<g3, kTileThreads, 0, stream>>>(p.decision, vocab, target_logits, q_probs, p.tile_sums);
+    GS_LAUNCH_CHECK("residual_tiles");
+    pick_token_kernel<true><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
+                                                                    q_probs, p.tile_sums, u_resample, out->next_token);
+  } else {
+    residual_tiles_kernel<false><<<g3, kTileThreads, 0, stream>>>(p.decision, vocab, target_logits, q_probs, p.tile_sums);
+    GS_LAUNCH_CHECK("residual_tiles");
+    pick_token_kernel<false><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
+                                                                     q_probs, p.tile_sums, u_resample, out->next_token);
+  }
+  GS_LAUNCH_CHECK("pick_token");
+  return GS_OK;
+}
+
+size_t accept_workspace_bytes(int n_servers, int n_rows, int vocab) {
+  return plan_accept(n_servers, n_rows, vocab, nullptr).bytes;
+}
+
+}  // namespace gs
+
+extern "C" size_t gs_accept_workspace_bytes(int n_servers, int n_rows, int vocab) {
+  if (n_servers <= 0 || n_rows <= 0 || vocab <= 0) return 0;
+  return gs::accept_workspace_bytes(n_servers, n_rows, vocab);
+}
+
+extern "C" gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                                      const float* target_logits, const float* q_probs, const int* draft_tokens,
+                                      const float* u_accept, const float* u_resample, const gs_accept_out* out,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (n_servers <= 0 || vocab <= 0) return gs::fail(GS_EINVAL, "n_servers and vocab must be positive");
+  if (!gamma_host || !cu_rows || !target_logits || !u_resample || !out || !workspace)
+    return gs::fail(GS_EINVAL, "null argument");
+  if (!out->accepted_len || !out->next_token || !out->accept_stat)
+    return gs::fail(GS_EINVAL, "accepted_len, next_token and accept_stat outputs are required");
+  long n_rows = 0, n_draft = 0;
+  for (int i = 0; i < n_servers; ++i) {
+    if (gamma_host[i] < 0) return gs::fail(GS_EINVAL, "gamma[%d] = %d is negative", i, gamma_host[i]);
+    n_rows += gamma_host[i] + 1;
+    n_draft += gamma_host[i];
+  }
+  if (n_rows > 0x3fffffff) return gs::fail(GS_EINVAL, "too many rows");
+  if (n_draft > 0 && (!q_probs || !draft_tokens || !u_accept))
+    return gs::fail(GS_EINVAL, "q_probs, draft_tokens and u_accept are required when any gamma > 0");
+  if (workspace_bytes < gs::accept_workspace_bytes(n_servers, (int)n_rows, vocab))
+    return gs::fail(GS_ECAPACITY, "workspace of %zu bytes is smaller than gs_accept_workspace_bytes", workspace_bytes);
+  return gs::launch_accept(n_servers, (int)n_rows, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept,
+                           u_resample, out, workspace, static_cast<hipStream_t>(hip_stream));
+}

@@ -1,0 +1,88 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-only entry points
+(the scheduler, argument validation) are exercised against the oracle.  No GPU needed."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import schedule as sch
+from paper_2512_09963_amd import binding as gsb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "goodspeed.h")).read()
+    declared = set(re.findall(r"\b(gs_[a-z_]+)\s*\(", header))
+    assert declared == set(gsb.EXPORTS)
+    L = gsb.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_schedule_gamma_equals_oracle(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 40))
+    gmin = int(rng.integers(0, 2))
+    gmax = int(rng.choice([-1, 6, 16]))
+    C = int(rng.integers(n * gmin, 12 * n + 1))
+    g_prev = rng.integers(0, 9, n)
+    m = np.array([rng.integers(0, g + 1) for g in g_prev])
+    stat = rng.random(n).astype(np.float32)
+    a0 = rng.uniform(0.05, 0.99, n)
+    X0 = rng.uniform(0.3, 8.0, n)
+    eta, beta = float(rng.uniform(0.05, 0.9)), float(rng.uniform(0.05, 0.9))
+    a_w, X_w, g_w = sch.schedule_round(m, stat, g_prev, a0, X0, eta, beta, C, gmin, None if gmax < 0 else gmax)
+    a, X = a0.copy(), X0.copy()
+    g = gsb.gs_schedule_gamma(m, stat, g_prev, a, X, eta, beta, C, gmin, gmax)
+    np.testing.assert_allclose(a, a_w, rtol=1e-15)
+    np.testing.assert_allclose(X, X_w, rtol=1e-15)
+    if not np.array_equal(g, g_w):       # several maximisers exist only on exact ties: compare what is unique
+        hi = None if gmax < 0 else gmax
+        assert sch.objective(a_w, X_w, g) == pytest.approx(sch.objective(a_w, X_w, g_w), rel=1e-13)
+        assert g.sum() == g_w.sum() and g.min() >= gmin and (hi is None or g.max() <= hi)
+    else:
+        assert g.sum() == (C if gmax < 0 else min(C, n * gmax))
+
+
+def test_schedule_gamma_hand_cases_and_ties():
+    a, X = np.array([0.5, 0.8]), np.array([1.0, 1.0])
+    # eta = beta = 0 leaves the state as given: gains 0.8, 0.64, 0.512 beat 0.5
+    g = gsb.gs_schedule_gamma([0, 0], [0, 0], [1, 1], a, X, 0.0, 0.0, 3)
+    np.testing.assert_array_equal(g, [0, 3])
+    a, X = np.array([0.7] * 3), np.array([2.0] * 3)
+    np.testing.assert_array_equal(gsb.gs_schedule_gamma([0] * 3, [0] * 3, [1] * 3, a, X, 0.0, 0.0, 4), [2, 1, 1])
+    a, X = np.array([0.5, 0.5]), np.array([1.0, 1.0])
+    g = gsb.gs_schedule_gamma([3, 0], [1.0, 0.0], [3, 3], a, X, 0.2, 0.5, 4)
+    np.testing.assert_allclose(a, [0.6, 0.4]); np.testing.assert_allclose(X, [2.5, 1.0])
+    np.testing.assert_array_equal(g, [2, 2])
+
+
+def test_schedule_gamma_rejects_bad_arguments():
+    a, X = np.array([0.5]), np.array([1.0])
+    with pytest.raises(gsb.GsError) as e:
+        gsb.gs_schedule_gamma([2], [0.5], [1], a, X, 0.2, 0.5, 4)
+    assert e.value.code == -1 and "accepted_len" in str(e.value)
+    with pytest.raises(gsb.GsError):
+        gsb.gs_schedule_gamma([0], [0.5], [1], a, X, 1.5, 0.5, 4)
+    with pytest.raises(gsb.GsError):
+        gsb.gs_schedule_gamma([0], [0.5], [1], a, X, 0.2, 0.5, 0, gamma_min=1)
+    np.testing.assert_array_equal(a, [0.5])          # a failed call changed nothing
+
+
+def test_accept_reject_validates_on_the_host_before_any_launch():
+    L = gsb.lib()
+    assert L.gs_accept_workspace_bytes(64, 576, 151936) > 0
+    assert L.gs_accept_workspace_bytes(0, 576, 151936) == 0
+    g = np.array([1, -2], dtype=np.int32)
+    rc = L.gs_accept_reject(2, g.ctypes.data, 8, 16, 8, 8, 8, 8, 8, None, 8, 0, None)
+    assert rc == -1
+    out = gsb.gs_accept_out(8, 8, 8, None)
+    import ctypes as C
+    rc = L.gs_accept_reject(2, g.ctypes.data, 8, 16, 8, 8, 8, 8, 8, C.byref(out), 8, 0, None)
+    assert rc == -1 and b"gamma[1]" in L.gs_last_error()
+    g[1] = 2
+    rc = L.gs_accept_reject(2, g.ctypes.data, 8, 16, 8, 8, 8, 8, 8, C.byref(out), 8, 16, None)
+    assert rc == -3
