@@ -1,0 +1,202 @@
+// Dense projections Y = X * W^T of the decoder (QKV, O, gate/up, down, LM head).
+//
+// bf16 path (MFMA): the verify step has few rows (tens to a few hundred) against
+// matrices of 10^7..10^9 weights, so every weight byte is used by only M rows: the kernel
+// is a weight-streaming kernel bound by HBM, and the layout serves the stream:
+//   * each wavefront owns 16 output columns; a lane reads 32 contiguous bytes of one weight
+//     row per 64-wide k step straight into the MFMA B operand (no LDS hop for weights), so a
+//     wave's loads cover 16 rows x 128 contiguous bytes; DEPTH steps are kept in flight
+//   * the activations (all M rows of the k step, at most 128) are staged once per workgroup
+//     in LDS (padded rows: conflict-free 16-byte reads) and shared by the four waves
+//   * K is split across workgroups when N alone gives too few of them to fill 256 CUs; the
+//     fp32 partial sums [S][M][N] are summed by the consumer kernel, in a fixed order.
+// k order inside a step is permuted identically for both operands (lane group g takes
+// k = 16g .. 16g+15, first half to the first MFMA, second half to the second), which leaves
+// the dot products unchanged.
+//
+// fp32 path: plain LDS-tiled FMA kernel for the small fp32 configuration.
+#include "common.h"
+#include "device_types.h"
+
+namespace gs {
+namespace {
+
+constexpr int kGemmThreads = 256;
+constexpr int kBK = 64;           // k elements per step
+constexpr int kLdsRow = kBK + 8;  // padded LDS row (bf16 elements): 144 bytes
+
+template <int MT, int DEPTH>
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf16_t* __restrict__ X,
+                                                                        const bf16_t* __restrict__ W,
+                                                                        float* __restrict__ P, int M, int N, int K,
+                                                                        int k_per_split) {
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int n0 = blockIdx.x * 64 + wave * 16;
+  const int split = blockIdx.y;
+  const int m0 = blockIdx.z * (MT * 16);
+  const int k_begin = split * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  const int n_steps = (k_end - k_begin) / kBK;
+
+  // activation tile: MT*16 rows x 64 k = MT*128 chunks of 16 bytes
+  constexpr int kChunks = MT * 128;
+  constexpr int kPasses = (kChunks + kGemmThreads - 1) / kGemmThreads;
+  uint4 xreg[kPasses];
+  auto load_x = [&](int step) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * kGemmThreads;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ch < kChunks && m0 + row < M)
+        v = *reinterpret_cast<const uint4*>(X + (size_t)(m0 + row) * K + k_begin + step * kBK + col);
+      xreg[p] = v;
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * kGemmThreads;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[p];
+    }
+  };
+
+  const bf16_t* wrow = W + (size_t)(n0 + c) * K + k_begin + g * 16;
+  uint4 wreg[DEPTH][2];
+  auto load_w = [&](int slot, int step) {
+    const uint4* p = reinterpret_cast<const uint4*>(wrow + (size_t)step * kBK);
+    wreg[slot][0] = p[0];
+    wreg[slot][1] = p[1];
+  };
+
+  floatx4_t acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < n_steps) load_w(d, d);
+  if (n_steps > 0) load_x(0);
+
+  for (int base = 0; base < n_steps; base += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int step = base + d;
+      if (step < n_steps) {
+        const int buf = step & 1;
+        store_x(buf);
+        __syncthreads();
+        if (step + 1 < n_steps) load_x(step + 1);
+        const uint4 w0 = wreg[d][0], w1 = wreg[d][1];
+        if (step + DEPTH < n_steps) load_w(d, step + DEPTH);
+        const bf16x8_t b0 = *reinterpret_cast<const bf16x8_t*>(&w0);
+        const bf16x8_t b1 = *reinterpret_cast<const bf16x8_t*>(&w1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const bf16_t* ap = &xs[buf][(mt * 16 + c) * kLdsRow + g * 16];
+          const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(ap);
+          const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(ap + 8);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0, acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, acc[mt], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  float* out = P + (size_t)split * M * N;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = m0 + mt * 16 + g * 4 + i;
+      if (row < M) out[(size_t)row * N + n0 + c] = acc[mt][i];
+    }
+  }
+}
+
+// fp32: 64x64 output tile, k step 16, each of 256 threads owns a 4x4 block.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ X, const float* __restrict__ W,
+                                                       float* __restrict__ Y, int M, int N, int K) {
+  __shared__ float xs[16][64 + 1], ws[16][64 + 1];
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int e = tid; e < 64 * 16; e += 256) {
+      const int r = e >> 4, kk = e & 15;
+      xs[kk][r] = (m0 + r < M && k0 + kk < K) ? X[(size_t)(m0 + r) * K + k0 + kk] : 0.f;
+      ws[kk][r] = (n0 + r < N && k0 + kk < K) ? W[(size_t)(n0 + r) * K + k0 + kk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = xs[kk][ty * 4 + i];
+        b[i] = ws[kk][tx * 4 + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = m0 + ty * 4 + i, cc = n0 + tx * 4 + j;
+      if (r < M && cc < N) Y[(size_t)r * N + cc] = acc[i][j];
+    }
+}
+
+}  // namespace
+
+// Number of K splits the bf16 kernel will use for this shape (1 for fp32).
+int gemm_splits(int dtype, int M, int N, int K) {
+  if (dtype != GS_BF16) return 1;
+  const int n_blocks = N / 64;
+  const int m_chunks = ceil_div(M, 128);
+  int want = ceil_div(768, n_blocks * m_chunks);     // about three workgroups per CU
+  int max_s = K / 512 > 0 ? K / 512 : 1;              // at least 8 steps per split
+  int s = want < max_s ? want : max_s;
+  if (s < 1) s = 1;
+  const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
+  return ceil_div(K, k_per);
+}
+
+// P [splits][M][N] fp32 partial sums of X [M][K] * W[N][K]^T.
+gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream) {
+  if (M <= 0) return GS_OK;
+  if (dtype == GS_BF16) {
+    const int s = gemm_splits(dtype, M, N, K);
+    const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
+    const bf16_t* x = static_cast<const bf16_t*>(X);
+    const bf16_t* w = static_cast<const bf16_t*>(W);
+    const int tiles = ceil_div(M, 16);
+    if (tiles <= 1) {
+      gemm_bf16_skinny_kernel<1, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+    } else if (tiles <= 2) {
+      gemm_bf16_skinny_kernel<2, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+    } else if (tiles <= 4) {
+      gemm_bf16_skinny_kernel<4, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+    } else {
+      gemm_bf16_skinny_kernel<8, 4><<<dim3(N / 64, s, ceil_div(M, 128)), kGemmThreads, 0, stream>>>(x, w, P, M, N, K,
+                                                                                                   k_per);
+    }
+    GS_LAUNCH_CHECK("gemm_bf16_skinny");
+  } else {
+    gemm_f32_kernel<<<dim3(ceil_div(N, 64), ceil_div(M, 64)), 256, 0, stream>>>(
+        static_cast<const float*>(X), static_cast<const float*>(W), P, M, N, K);
+    GS_LAUNCH_CHECK("gemm_f32");
+  }
+  return GS_OK;
+}
+
+}  // namespace gs

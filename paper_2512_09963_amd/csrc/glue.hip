@@ -1,0 +1,174 @@
+// Row-wise kernels between the projections of the decoder: embedding gather,
+// residual add + RMSNorm (also sums the split-K partials of the preceding projection),
+// rotary embedding + KV-page append, SwiGLU.  All arithmetic is fp32; T is the storage
+// type of the tensors fed to the next projection and of the KV pages (float or bf16).
+#include "common.h"
+#include "device_types.h"
+
+namespace gs {
+namespace {
+
+__device__ __forceinline__ float block_sum_256(float v, float* sh /*[4]*/) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+  __syncthreads();
+  return t;
+}
+
+// server that owns target row r: largest i with cu_rows[i] <= r
+__device__ __forceinline__ int server_of_row(const int* __restrict__ cu_rows, int n_servers, int r) {
+  int lo = 0, hi = n_servers;   // invariant: cu_rows[lo] <= r < cu_rows[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu_rows[mid] <= r) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ embed, const int* __restrict__ tokens,
+                                                    float* __restrict__ x, int d) {
+  const int r = blockIdx.x;
+  const T* src = embed + (size_t)tokens[r] * d;
+  for (int i = threadIdx.x; i < d; i += 256) x[(size_t)r * d + i] = Storage<T>::load(src + i);
+}
+
+// x[r] += sum_s partial[s][r] (if partial), then h[r] = x[r] * w / sqrt(mean(x[r]^2) + eps).
+template <typename T>
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ partial,
+                                                          int n_splits, int n_rows, const float* __restrict__ w,
+                                                          float eps, T* __restrict__ h, int d) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  float* xr = x + (size_t)r * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = xr[i];
+    if (partial) {
+      float add = 0.f;
+      for (int s = 0; s < n_splits; ++s) add += partial[((size_t)s * n_rows + r) * d + i];
+      v += add;
+      xr[i] = v;
+    }
+    ss += v * v;
+  }
+  const float tot = block_sum_256(ss, sh);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) Storage<T>::store(h + (size_t)r * d + i, xr[i] * inv * w[i]);
+}
+
+// Sums the QKV partials, rotates Q and K at the row's position, stores Q [R][H][hd] and
+// appends K ([page][H_kv][slot][hd]) and V ([page][H_kv][hd][slot]) to the layer's pages.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
+                                                          const int* __restrict__ cu_rows,
+                                                          const int* __restrict__ ctx_len, int n_servers,
+                                                          const int* __restrict__ block_table, int max_blocks,
+                                                          int page_size, int n_heads, int n_kv, int hd,
+                                                          float log2_theta, T* __restrict__ q_out,
+                                                          T* __restrict__ k_pages, T* __restrict__ v_pages) {
+  const int r = blockIdx.x;
+  const int srv = server_of_row(cu_rows, n_servers, r);
+  const int pos = ctx_len[srv] + (r - cu_rows[srv]);
+  const int page = block_table[(size_t)srv * max_blocks + pos / page_size];
+  const int slot = pos % page_size;
+  const int width = (n_heads + 2 * n_kv) * hd;
+  const int half = hd >> 1;
+  auto value = [&](int col) {
+    float v = 0.f;
+    for (int s = 0; s < n_splits; ++s) v += qkv[((size_t)s * n_rows + r) * width + col];
+    return v;
+  };
+  // rotated heads: Q heads then K heads, one (i, i + hd/2) pair per work item
+  const int n_rot = (n_heads + n_kv) * half;
+  for (int e = threadIdx.x; e < n_rot; e += 256) {
+    const int head = e / half, i = e - head * half;
+    const float inv_freq = exp2f(-2.0f * (float)i / (float)hd * log2_theta);
+    float sn, cs;
+    sincosf((float)pos * inv_freq, &sn, &cs);
+    const float a = value(head * hd + i), b = value(head * hd + i + half);
+    const float ra = a * cs - b * sn, rb = b * cs + a * sn;
+    if (head < n_heads) {
+      T* dst = q_out + ((size_t)r * n_heads + head) * hd;
+      Storage<T>::store(dst + i, ra);
+      Storage<T>::store(dst + i + half, rb);
+    } else {
+      const int kh = head - n_heads;
+      T* dst = k_pages + (((size_t)page * n_kv + kh) * page_size + slot) * hd;
+      Storage<T>::store(dst + i, ra);
+      Storage<T>::store(dst + i + half, rb);
+    }
+  }
+  const int v_col0 = (n_heads + n_kv) * hd;
+  for (int e = threadIdx.x; e < n_kv * hd; e += 256) {
+    const int kh = e / hd, dd = e - kh * hd;
+    Storage<T>::store(v_pages + (((size_t)page * n_kv + kh) * hd + dd) * page_size + slot, value(v_col0 + e));
+  }
+}
+
+// act[r][f] = silu(gate) * up with gate = sum_s gu[s][r][f], up = sum_s gu[s][r][F + f].
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int n_splits, int n_rows, int F,
+                                                     T* __restrict__ act) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)n_rows * F) return;
+  const int r = (int)(idx / F), f = (int)(idx - (size_t)r * F);
+  float gt = 0.f, up = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float* row = gu + ((size_t)s * n_rows + r) * 2 * F;
+    gt += row[f];
+    up += row[F + f];
+  }
+  Storage<T>::store(act + idx, gt / (1.0f + expf(-gt)) * up);
+}
+
+}  // namespace
+
+#define GS_DISPATCH_T(dtype, ...)                 \
+  if ((dtype) == GS_BF16) {                       \
+    using T = bf16_t;                             \
+    __VA_ARGS__                                   \
+  } else {                                        \
+    using T = float;                              \
+    __VA_ARGS__                                   \
+  }
+
+gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d,
+                       hipStream_t stream) {
+  GS_DISPATCH_T(dtype, embed_kernel<T><<<n_rows, 256, 0, stream>>>(static_cast<const T*>(embed), tokens, x, d);)
+  GS_LAUNCH_CHECK("embed");
+  return GS_OK;
+}
+
+gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
+                             float eps, void* h, int d, hipStream_t stream) {
+  GS_DISPATCH_T(dtype, add_rmsnorm_kernel<T><<<n_rows, 256, 0, stream>>>(x, partial, n_splits, n_rows, w, eps,
+                                                                        static_cast<T*>(h), d);)
+  GS_LAUNCH_CHECK("add_rmsnorm");
+  return GS_OK;
+}
+
+gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const int* cu_rows,
+                             const int* ctx_len, int n_servers, const int* block_table, int max_blocks,
+                             int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
+                             void* k_pages, void* v_pages, hipStream_t stream) {
+  const float log2_theta = log2f(rope_theta);
+  GS_DISPATCH_T(dtype, rope_append_kernel<T><<<n_rows, 256, 0, stream>>>(
+                           qkv, n_splits, n_rows, cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size,
+                           n_heads, n_kv, hd, log2_theta, static_cast<T*>(q_out), static_cast<T*>(k_pages),
+                           static_cast<T*>(v_pages));)
+  GS_LAUNCH_CHECK("rope_append");
+  return GS_OK;
+}
+
+gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream) {
+  const size_t total = (size_t)n_rows * F;
+  const int blocks = (int)((total + 255) / 256);
+  GS_DISPATCH_T(dtype, swiglu_kernel<T><<<blocks, 256, 0, stream>>>(gu, n_splits, n_rows, F, static_cast<T*>(act));)
+  GS_LAUNCH_CHECK("swiglu");
+  return GS_OK;
+}
+
+}  // namespace gs

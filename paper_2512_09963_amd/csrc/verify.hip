@@ -1,0 +1,264 @@
+// gs_verify_batch: the decoder forward over the ragged speculative blocks followed by
+// rejection-verification, enqueued on one stream without host synchronisation.
+// Per layer: add+RMSNorm -> QKV projection -> rotary + KV append -> attention -> O projection
+//            -> add+RMSNorm -> gate/up projection -> SwiGLU -> down projection.
+// The residual stream and the logits are fp32; tensors fed to a projection and the KV
+// pages are in the model's storage type.
+#include <new>
+#include <vector>
+#include "common.h"
+
+namespace gs {
+
+int gemm_splits(int dtype, int M, int N, int K);
+gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream);
+gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
+gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
+                             float eps, void* h, int d, hipStream_t stream);
+gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const int* cu_rows,
+                             const int* ctx_len, int n_servers, const int* block_table, int max_blocks,
+                             int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
+                             void* k_pages, void* v_pages, hipStream_t stream);
+gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
+int attention_splits(int n_servers, int n_kv, int max_ctx);
+size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int n_splits);
+gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
+                           const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
+                           int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
+                           int max_block_tokens, int n_splits, float* scratch, void* attn_out, hipStream_t stream);
+gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
+                        const float* q_probs, const int* draft_tokens, const float* u_accept,
+                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream);
+size_t accept_workspace_bytes(int n_servers, int n_rows, int vocab);
+
+}  // namespace gs
+
+struct gs_ctx {
+  gs_model_desc desc;
+  const void* embed;
+  const void* lm_head;
+  const float* final_norm;
+  std::vector<const void*> wqkv, wo, wgu, wd;
+  std::vector<const float*> norm1, norm2;
+  size_t elem;   // bytes per stored element
+};
+
+namespace {
+
+struct Plan {
+  float* x;
+  void* h;
+  float* partial;
+  void* q;
+  void* attn;
+  void* act;
+  float* attn_scratch;
+  float* logits;
+  int* draft_tokens;
+  void* accept_ws;
+  size_t bytes;
+};
+
+size_t max_partial_floats(const gs_model_desc& m, int max_rows) {
+  const int qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
+  const int hq = m.n_heads * m.head_dim;
+  size_t best = 0;
+  for (int M = 1; M <= max_rows; ++M) {
+    size_t a = (size_t)gs::gemm_splits(m.dtype, M, qkv, m.d_model) * M * qkv;
+    size_t b = (size_t)gs::gemm_splits(m.dtype, M, m.d_model, hq) * M * m.d_model;
+    size_t c = (size_t)gs::gemm_splits(m.dtype, M, 2 * m.d_ffn, m.d_model) * M * 2 * m.d_ffn;
+    size_t d = (size_t)gs::gemm_splits(m.dtype, M, m.d_model, m.d_ffn) * M * m.d_model;
+    const int sv = gs::gemm_splits(m.dtype, M, m.vocab, m.d_model);
+    size_t e = sv > 1 ? (size_t)sv * M * m.vocab : 0;   // LM head partials only when it is split
+    best = std::max(std::max(best, a), std::max(std::max(b, e), std::max(c, d)));
+  }
+  return best;
+}
+
+Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, void* ws) {
+  const gs_model_desc& m = ctx->desc;
+  const size_t R = max_rows;
+  const int hq = m.n_heads * m.head_dim;
+  gs::Carver c(ws);
+  Plan p;
+  p.x = c.take<float>(R * m.d_model);
+  p.h = c.take<char>(R * m.d_model * ctx->elem);
+  p.partial = c.take<float>(max_partial_floats(m, max_rows));
+  p.q = c.take<char>(R * hq * ctx->elem);
+  p.attn = c.take<char>(R * hq * ctx->elem);
+  p.act = c.take<char>(R * m.d_ffn * ctx->elem);
+  int max_splits = 1;
+  for (int n = 1; n <= max_servers; ++n)
+    max_splits = std::max(max_splits, gs::attention_splits(n, m.n_kv_heads, max_ctx));
+  p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
+  p.logits = c.take<float>(R * m.vocab);
+  p.draft_tokens = c.take<int>(R);
+  size_t acc = 0;
+  for (int n = 1; n <= max_servers; ++n) acc = std::max(acc, gs::accept_workspace_bytes(n, max_rows, m.vocab));
+  p.accept_ws = c.take<char>(acc);
+  p.bytes = c.used();
+  return p;
+}
+
+// y[i] = sum_s partial[s][i]
+__global__ void sum_partials_kernel(const float* __restrict__ partial, int n_splits, size_t n, float* __restrict__ y) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) acc += partial[(size_t)s * n + i];
+  y[i] = acc;
+}
+
+// draft_tokens[cu_rows[i] - i + j] = tokens[cu_rows[i] + 1 + j]: the drafts without the pending tokens
+__global__ void gather_draft_tokens_kernel(const int* __restrict__ tokens, const int* __restrict__ cu_rows,
+                                           int n_servers, int* __restrict__ draft_tokens) {
+  const int srv = blockIdx.x;
+  const int r0 = cu_rows[srv], gamma = cu_rows[srv + 1] - r0 - 1;
+  for (int j = threadIdx.x; j < gamma; j += blockDim.x) draft_tokens[r0 - srv + j] = tokens[r0 + 1 + j];
+}
+
+}  // namespace
+
+extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, gs_ctx** out) {
+  if (!desc || !w || !out) return gs::fail(GS_EINVAL, "null argument");
+  const gs_model_desc& m = *desc;
+  if (m.n_layers <= 0 || m.d_model <= 0 || m.n_heads <= 0 || m.n_kv_heads <= 0 || m.head_dim <= 0 || m.d_ffn <= 0 ||
+      m.vocab <= 0)
+    return gs::fail(GS_EINVAL, "model dimensions must be positive");
+  if (m.dtype != GS_F32 && m.dtype != GS_BF16) return gs::fail(GS_EINVAL, "dtype must be GS_F32 or GS_BF16");
+  if (m.head_dim != 64 && m.head_dim != 128) return gs::fail(GS_ESHAPE, "head_dim must be 64 or 128");
+  if (m.n_heads % m.n_kv_heads != 0) return gs::fail(GS_ESHAPE, "n_heads must be a multiple of n_kv_heads");
+  const int group = m.n_heads / m.n_kv_heads;
+  if (group != 1 && group != 2 && group != 4 && group != 8) return gs::fail(GS_ESHAPE, "GQA group must be 1, 2, 4 or 8");
+  if (m.dtype == GS_BF16) {
+    const int qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
+    if (m.d_model % 64 || m.d_ffn % 64 || qkv % 64 || m.vocab % 64)
+      return gs::fail(GS_ESHAPE, "bf16 models need d_model, d_ffn, projection widths and vocab to be multiples of 64");
+  }
+  if (!(m.rope_theta > 1.f) || !(m.rms_eps >= 0.f)) return gs::fail(GS_EINVAL, "rope_theta must exceed 1, rms_eps >= 0");
+  if (!w->embed || !w->lm_head || !w->final_norm || !w->wqkv || !w->wo || !w->wgu || !w->wd || !w->norm1 || !w->norm2)
+    return gs::fail(GS_EINVAL, "null weight table");
+  for (int l = 0; l < m.n_layers; ++l)
+    if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wd[l] || !w->norm1[l] || !w->norm2[l])
+      return gs::fail(GS_EINVAL, "null weight pointer in layer %d", l);
+  gs_ctx* c = new (std::nothrow) gs_ctx;
+  if (!c) return gs::fail(GS_EINVAL, "out of host memory");
+  c->desc = m;
+  c->embed = w->embed;
+  c->lm_head = w->lm_head;
+  c->final_norm = w->final_norm;
+  c->wqkv.assign(w->wqkv, w->wqkv + m.n_layers);
+  c->wo.assign(w->wo, w->wo + m.n_layers);
+  c->wgu.assign(w->wgu, w->wgu + m.n_layers);
+  c->wd.assign(w->wd, w->wd + m.n_layers);
+  c->norm1.assign(w->norm1, w->norm1 + m.n_layers);
+  c->norm2.assign(w->norm2, w->norm2 + m.n_layers);
+  c->elem = m.dtype == GS_BF16 ? 2 : 4;
+  *out = c;
+  return GS_OK;
+}
+
+extern "C" gs_status gs_destroy(gs_ctx* ctx) {
+  delete ctx;
+  return GS_OK;
+}
+
+extern "C" size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx) {
+  if (!ctx || max_rows <= 0 || max_servers <= 0 || max_ctx <= 0) return 0;
+  return make_plan(ctx, max_rows, max_servers, max_ctx, nullptr).bytes;
+}
+
+extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* b, const gs_accept_out* out,
+                                     float* logits_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!ctx || !kv || !b || !workspace) return gs::fail(GS_EINVAL, "null argument");
+  const gs_model_desc& m = ctx->desc;
+  const int n = b->n_servers;
+  if (n <= 0) return gs::fail(GS_EINVAL, "n_servers must be positive");
+  if (!b->gamma_host || !b->ctx_len_host || !b->cu_rows || !b->ctx_len || !b->tokens || !b->block_table)
+    return gs::fail(GS_EINVAL, "null batch field");
+  if (!kv->k_pages || !kv->v_pages || kv->page_size <= 0 || kv->n_pages <= 0 || b->max_blocks <= 0)
+    return gs::fail(GS_EINVAL, "invalid KV cache descriptor");
+  if (m.dtype == GS_BF16 && kv->page_size % 16 != 0)
+    return gs::fail(GS_ESHAPE, "bf16 attention needs a page size that is a multiple of 16");
+  long R = 0, G = 0;
+  int max_t = 0, max_ctx = 0;
+  for (int i = 0; i < n; ++i) {
+    const int g = b->gamma_host[i], L = b->ctx_len_host[i];
+    if (g < 0 || L < 0) return gs::fail(GS_EINVAL, "server %d: gamma = %d, ctx_len = %d", i, g, L);
+    const long need = ((long)L + g + 1 + kv->page_size - 1) / kv->page_size;
+    if (need > b->max_blocks)
+      return gs::fail(GS_ECAPACITY, "server %d needs %ld KV blocks for %d + %d tokens, block table has %d", i, need, L,
+                      g + 1, b->max_blocks);
+    R += g + 1;
+    G += g;
+    max_t = std::max(max_t, g + 1);
+    max_ctx = std::max(max_ctx, L + g + 1);
+  }
+  if (R > (1 << 20)) return gs::fail(GS_EINVAL, "too many rows");
+  const bool do_accept = b->q_probs != nullptr;
+  if (do_accept) {
+    if (!out || !out->accepted_len || !out->next_token || !out->accept_stat)
+      return gs::fail(GS_EINVAL, "accept outputs are required when q_probs is given");
+    if (!b->u_resample || (G > 0 && !b->u_accept)) return gs::fail(GS_EINVAL, "uniforms are required");
+  }
+  const size_t need_ws = make_plan(ctx, (int)R, n, max_ctx, nullptr).bytes;
+  if (workspace_bytes < need_ws)
+    return gs::fail(GS_ECAPACITY, "workspace of %zu bytes, this batch needs %zu", workspace_bytes, need_ws);
+  const Plan p = make_plan(ctx, (int)R, n, max_ctx, workspace);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int rows = (int)R, d = m.d_model, hq = m.n_heads * m.head_dim, qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
+  const int F = m.d_ffn;
+  const size_t layer_stride = (size_t)kv->n_pages * m.n_kv_heads * kv->page_size * m.head_dim * ctx->elem;
+  const int attn_splits = gs::attention_splits(n, m.n_kv_heads, max_ctx);
+  gs_status st;
+#define GS_TRY(call)          \
+  do {                        \
+    st = (call);              \
+    if (st != GS_OK) return st; \
+  } while (0)
+
+  GS_TRY(gs::launch_embed(m.dtype, ctx->embed, b->tokens, p.x, rows, d, stream));
+  const float* pending = nullptr;   // split-K partials of the projection whose result is still to be added to x
+  int pending_splits = 0;
+  for (int l = 0; l < m.n_layers; ++l) {
+    GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
+    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
+    char* kl = static_cast<char*>(kv->k_pages) + layer_stride * l;
+    char* vl = static_cast<char*>(kv->v_pages) + layer_stride * l;
+    GS_TRY(gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, b->cu_rows,
+                                  b->ctx_len, n, b->block_table, b->max_blocks, kv->page_size, m.n_heads,
+                                  m.n_kv_heads, m.head_dim, m.rope_theta, p.q, kl, vl, stream));
+    GS_TRY(gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
+                                kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_splits,
+                                p.attn_scratch, p.attn, stream));
+    GS_TRY(gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
+    GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows, ctx->norm2[l],
+                                  m.rms_eps, p.h, d, stream));
+    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
+    GS_TRY(gs::launch_swiglu(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
+    GS_TRY(gs::launch_gemm(m.dtype, p.act, ctx->wd[l], p.partial, rows, d, F, stream));
+    pending = p.partial;
+    pending_splits = gs::gemm_splits(m.dtype, rows, d, F);
+  }
+  GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
+  float* logits = logits_out ? logits_out : p.logits;
+  const int lm_splits = gs::gemm_splits(m.dtype, rows, m.vocab, d);
+  if (lm_splits == 1) {
+    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->lm_head, logits, rows, m.vocab, d, stream));
+  } else {   // small vocabularies only: the partials fit the projection scratch
+    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->lm_head, p.partial, rows, m.vocab, d, stream));
+    const size_t n_out = (size_t)rows * m.vocab;
+    sum_partials_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, stream>>>(p.partial, lm_splits, n_out, logits);
+    GS_LAUNCH_CHECK("sum_partials");
+  }
+  if (do_accept) {
+    if (G > 0) {
+      gather_draft_tokens_kernel<<<n, 64, 0, stream>>>(b->tokens, b->cu_rows, n, p.draft_tokens);
+      GS_LAUNCH_CHECK("gather_draft_tokens");
+    }
+    GS_TRY(gs::launch_accept(n, rows, b->cu_rows, m.vocab, logits, b->q_probs, p.draft_tokens, b->u_accept,
+                             b->u_resample, out, p.accept_ws, stream));
+  }
+#undef GS_TRY
+  return GS_OK;
+}

@@ -240,18 +240,18 @@ def matrix(ms: ModelShape, seed, name, layer, shape, std=0.02):
     return w
 
 
-def layer_weights(ms: ModelShape, seed, layer):
+def layer_weights(ms: ModelShape, seed, layer, std=0.02):
     """Dict of one layer's tensors (float32 arrays holding storage-type values)."""
-    out = {k: matrix(ms, seed, k, layer, s) for k, s in layer_matrix_shapes(ms).items()}
+    out = {k: matrix(ms, seed, k, layer, s, std) for k, s in layer_matrix_shapes(ms).items()}
     out["norm1"] = np.ones(ms.d_model, dtype=np.float32)
     out["norm2"] = np.ones(ms.d_model, dtype=np.float32)
     return out
 
 
-def top_weights(ms: ModelShape, seed):
+def top_weights(ms: ModelShape, seed, std=0.02):
     return {
-        "embed": matrix(ms, seed, "embed", 0, (ms.vocab, ms.d_model)),
-        "lm_head": matrix(ms, seed, "lm_head", 0, (ms.vocab, ms.d_model)),
+        "embed": matrix(ms, seed, "embed", 0, (ms.vocab, ms.d_model), std),
+        "lm_head": matrix(ms, seed, "lm_head", 0, (ms.vocab, ms.d_model), std),
         "final_norm": np.ones(ms.d_model, dtype=np.float32),
     }
 
@@ -323,13 +323,12 @@ def log_uniform_int(seed, tags, lo, hi, n):
     return np.clip(np.round(np.exp(np.log(lo) + u * (np.log(hi) - np.log(lo)))), lo, hi).astype(np.int32)
 
 
-def verify_side_inputs(seed, ms_vocab, gamma, draft_mode="independent", target_logits=None,
-                       sigma=0.5, logit_scale=1.0, tag="vin"):
+def verify_side_inputs(seed, ms_vocab, gamma, sigma=0.5, logit_scale=1.0, tag="vin"):
     """Draft-side inputs of a full verify step: pending+draft token ids, q, uniforms.
 
-    draft_mode "independent": draft logits = logit_scale * (z + sigma * eps) with z, eps
-    standard normal per row, independent of the target model.  The draft tokens are
-    sampled from q; the pending token of each server is uniform over the vocabulary.
+    Draft logits = logit_scale * (z + sigma * eps) with z, eps standard normal per row,
+    independent of the target model.  The draft tokens are sampled from q; the pending
+    token of each server is uniform over the vocabulary.
     Returns (tokens[R], q_probs[Gamma, V], u_accept[Gamma], u_resample[N]).
     """
     gamma = np.asarray(gamma, dtype=np.int32)

@@ -1,0 +1,169 @@
+"""Parity of gs_verify_batch (HIP, through the C ABI) with the forward + accept oracle.
+
+Tolerances (relative to the row scale max|logit|, see tests/parity.py for the decisions):
+fp32 models 1e-4, bf16 models 2e-2.
+"""
+import numpy as np
+import pytest
+
+from oracle import accept_reject as ar
+from oracle import forward as fw
+from paper_2512_09963_amd import synth
+from tests.parity import check_accept_outputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def assert_logits_close(got, want, tol, what="logits"):
+    scale = np.abs(want).max(axis=1, keepdims=True)
+    err = np.abs(got.astype(np.float64) - want) / scale
+    worst = err.max()
+    assert worst <= tol, f"{what}: max |diff| / row scale = {worst:.3g} > {tol:g} (row {int(err.max(axis=1).argmax())})"
+    return worst
+
+
+def _model(ms, seed, std):
+    top = synth.top_weights(ms, seed, std)
+    layers = [synth.layer_weights(ms, seed, l, std) for l in range(ms.n_layers)]
+    return top, layers
+
+
+def _oracle_cache(ms, seed, n_pages, page, synthetic):
+    out = []
+    for l in range(ms.n_layers):
+        if synthetic:
+            out.append((synth.kv_layer_cache(ms, seed, l, "k", n_pages, page),
+                        synth.kv_layer_cache(ms, seed, l, "v", n_pages, page)))
+        else:
+            shape = (n_pages, ms.n_kv_heads, page, ms.head_dim)
+            out.append((np.zeros(shape, np.float32), np.zeros(shape, np.float32)))
+    return out
+
+
+def _check_kv_rows(ms, kv_dev, cache, batch, tol):
+    """The block's appended K/V rows agree with the oracle's."""
+    for l in range(ms.n_layers):
+        k_g, v_g = kv_dev.get_layer(l)
+        for i in range(batch.n_servers):
+            for pos in range(int(batch.ctx_len[i]), int(batch.ctx_len[i] + batch.gamma[i] + 1)):
+                pg, sl = int(batch.block_table[i, pos // batch.page_size]), pos % batch.page_size
+                for got, want, name in ((k_g, cache[l][0], "K"), (v_g, cache[l][1], "V")):
+                    w = want[pg, :, sl, :].astype(np.float64)
+                    g = got[pg, :, sl, :].astype(np.float64)
+                    assert np.abs(g - w).max() <= tol * max(np.abs(w).max(), 1e-6) + 1e-7, \
+                        f"{name} layer {l} server {i} pos {pos}"
+
+
+def _run_case(ms, seed, gamma, ctx_len, page, std, synthetic_kv=True, permute=True, sigma=0.5):
+    import torch
+    from paper_2512_09963_amd import workload as wl
+    tol = TOL[ms.dtype]
+    top, layers = _model(ms, seed, std)
+    batch = synth.make_batch(seed, gamma, ctx_len, page, permute_pages=permute)
+    tokens, q, ua, ur = synth.verify_side_inputs(seed, ms.vocab, batch.gamma, sigma=sigma)
+    cache = _oracle_cache(ms, seed, batch.n_pages, page, synthetic_kv)
+    ver = wl.upload_model(ms, top, lambda l: layers[l])
+    kv = wl.KVCache(ms, batch.n_pages, page)
+    for l in range(ms.n_layers):
+        kv.set_layer(l, cache[l][0], cache[l][1])
+    db = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    out, logits, _ = wl.verify(ver, kv, db)
+    torch.cuda.synchronize()
+    got_logits = logits.cpu().numpy()
+    want_logits = fw.verify_forward(ms, tokens, batch.gamma, batch.ctx_len, batch.block_table, page, top,
+                                    lambda l: layers[l], lambda l: cache[l])
+    worst = assert_logits_close(got_logits, want_logits, tol)
+    _check_kv_rows(ms, kv, cache, batch, tol)
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    cu = batch.cu_rows
+    d_tok = np.concatenate([tokens[cu[i] + 1:cu[i + 1]] for i in range(batch.n_servers)]) if batch.n_draft else np.zeros(0, np.int32)
+    # teacher-forced: the oracle's accept stage on the GPU's own logits must agree outside the bands
+    bands = check_accept_outputs(batch.gamma, got_logits, q, d_tok, ua, ur, got)
+    return dict(worst=worst, bands=bands, got=got, want_logits=want_logits, q=q, d_tok=d_tok, ua=ua, ur=ur,
+                batch=batch)
+
+
+def test_config1_tiny_fp32_with_real_prefill():
+    """2 layers, d 256, 4 heads of 64, FFN 1024, vocab 1024; 4 servers, gamma [2,3,4,5], 64-token prefixes
+    that both sides prefill themselves (the GPU through gs_verify_batch with 64-row blocks)."""
+    import torch
+    from paper_2512_09963_amd import workload as wl
+    ms, seed, page = synth.TINY, synth.MASTER_SEED, 16
+    top, layers = _model(ms, seed, 0.02)
+    gamma, ctx = np.array([2, 3, 4, 5], np.int32), np.full(4, 64, np.int32)
+    batch = synth.make_batch(seed, gamma, ctx, page, permute_pages=True)
+    prefix = synth.uniform_int(seed, ("prefix",), 0, ms.vocab - 1, 4 * 64)
+    pre_batch = synth.BatchShape(np.full(4, 63, np.int32), np.zeros(4, np.int32), page, batch.block_table, batch.n_pages)
+    cache = _oracle_cache(ms, seed, batch.n_pages, page, synthetic=False)
+    want_pre = fw.verify_forward(ms, prefix, pre_batch.gamma, pre_batch.ctx_len, batch.block_table, page, top,
+                                 lambda l: layers[l], lambda l: cache[l])
+    ver = wl.upload_model(ms, top, lambda l: layers[l])
+    kv = wl.KVCache(ms, batch.n_pages, page)
+    _, logits_pre, _ = wl.verify(ver, kv, wl.DeviceBatch(pre_batch, prefix))
+    torch.cuda.synchronize()
+    assert_logits_close(logits_pre.cpu().numpy(), want_pre, 1e-4, "prefill logits")
+
+    tokens, q, ua, ur = synth.verify_side_inputs(seed, ms.vocab, gamma, sigma=0.5)
+    out, logits, _ = wl.verify(ver, kv, wl.DeviceBatch(batch, tokens, q, ua, ur))
+    torch.cuda.synchronize()
+    want = fw.verify_forward(ms, tokens, gamma, ctx, batch.block_table, page, top, lambda l: layers[l], lambda l: cache[l])
+    got_logits = logits.cpu().numpy()
+    assert_logits_close(got_logits, want, 1e-4)
+    _check_kv_rows(ms, kv, cache, batch, 1e-4)
+    p_got = np.stack([ar.softmax(r) for r in got_logits]); p_want = np.stack([ar.softmax(r) for r in want])
+    assert np.all(np.abs(p_got - p_want) <= 1e-4 * np.maximum(p_want, 1.0 / ms.vocab))
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    cu = batch.cu_rows
+    d_tok = np.concatenate([tokens[cu[i] + 1:cu[i + 1]] for i in range(4)])
+    check_accept_outputs(gamma, got_logits, q, d_tok, ua, ur, got)            # teacher-forced
+    check_accept_outputs(gamma, want.astype(np.float32), q, d_tok, ua, ur, got)  # fully independent end to end
+
+
+@pytest.mark.parametrize("name,ms", [
+    ("g4_hd128", synth.ModelShape(2, 256, 4, 1, 128, 512, 1024, 500000.0, dtype="bf16")),
+    ("g2_hd64", synth.ModelShape(2, 256, 8, 4, 64, 512, 1024, 10000.0, dtype="bf16")),
+    ("g8_hd128", synth.ModelShape(1, 256, 8, 1, 128, 384, 2048, 500000.0, dtype="bf16")),
+    ("g1_hd128", synth.ModelShape(1, 128, 2, 2, 128, 256, 1024, 500000.0, dtype="bf16")),
+])
+def test_small_bf16_models_ragged_paged(name, ms):
+    gamma = np.array([0, 16, 3, 7, 1, 5], np.int32)
+    ctx = np.array([5, 40, 300, 1000, 17, 0], np.int32)
+    r = _run_case(ms, 77, gamma, ctx, 16, std=0.08)
+    print(name, "worst logits error / scale:", r["worst"], r["bands"])
+
+
+def test_small_f32_model_with_gqa_and_page_32():
+    ms = synth.ModelShape(2, 128, 4, 2, 64, 256, 500, 10000.0, dtype="f32")
+    r = _run_case(ms, 78, np.array([3, 0, 6], np.int32), np.array([33, 2, 130], np.int32), 32, std=0.08)
+    print("worst", r["worst"])
+
+
+def test_bf16_page_size_64_and_single_server():
+    ms = synth.ModelShape(1, 256, 4, 1, 128, 512, 1024, 500000.0, dtype="bf16")
+    _run_case(ms, 79, np.array([8], np.int32), np.array([700], np.int32), 64, std=0.08)
+
+
+def test_verify_batch_rejects_bad_descriptors():
+    import torch
+    from paper_2512_09963_amd import binding as gsb, workload as wl
+    ms = synth.ModelShape(1, 128, 2, 2, 64, 256, 512, 10000.0, dtype="f32")
+    top, layers = _model(ms, 3, 0.02)
+    ver = wl.upload_model(ms, top, lambda l: layers[l])
+    batch = synth.make_batch(3, np.array([2, 2], np.int32), np.array([10, 10], np.int32), 16)
+    tokens, q, ua, ur = synth.verify_side_inputs(3, ms.vocab, batch.gamma)
+    kv = wl.KVCache(ms, batch.n_pages, 16)
+    db = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    small = torch.empty(64, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(gsb.GsError) as e:
+        wl.verify(ver, kv, db, workspace=small)
+    assert e.value.code == -3
+    db.ctx_len_host = np.array([10, 1000], np.int32)          # needs more blocks than the table has
+    with pytest.raises(gsb.GsError) as e:
+        wl.verify(ver, kv, db)
+    assert e.value.code == -3 and "KV blocks" in str(e.value)
+    with pytest.raises(gsb.GsError) as e:
+        gsb.Verifier(dict(n_layers=1, d_model=100, n_heads=3, n_kv_heads=2, head_dim=64, d_ffn=256, vocab=512,
+                          rope_theta=1e4, rms_eps=1e-5, dtype="f32"), ver._keep[0], ver._keep[1])
+    assert e.value.code == -2
