@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification step on one MI355X.
+
+A step is one pass of the whole hot path on one batch of synthetic input:
+gs_verify_batch (decoder forward over the ragged blocks + rejection-verification),
+the copy of the 3N result scalars to the host, and gs_schedule_gamma.
+
+Workload (default): Llama-3-8B-shaped random-init bf16 decoder, 8 draft servers with
+gamma drawn uniformly from [3, 8], 2048 cached tokens per server in 16-token pages.
+Prints one JSON line; `value` is verified draft tokens per second (sum(gamma) / step time).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (result is marked invalid)")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-accept-leg", action="store_true")
+    return ap.parse_args()
+
+
+def build_workload(ms, seed):
+    import torch
+    from paper_2512_09963_amd import synth, workload as wl
+    n = 8
+    gamma = synth.uniform_int(seed, ("cfg3", "gamma"), 3, 8, n)
+    ctx = np.full(n, 2048, np.int32)
+    batch = synth.make_batch(seed, gamma, ctx, 16, permute_pages=False)
+    tokens, q, ua, ur = synth.verify_side_inputs(seed, ms.vocab, gamma, sigma=0.5, tag="cfg3")
+    t0 = time.time()
+    top = synth.top_weights(ms, seed)
+    ver = wl.upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l))
+    kv = wl.KVCache(ms, batch.n_pages, 16, zero=False)
+    for l in range(ms.n_layers):
+        kv.set_layer(l, synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, 16),
+                     synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, 16))
+    torch.cuda.synchronize()
+    print(f"[bench] weights + KV generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    db = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    return dict(ver=ver, kv=kv, db=db, batch=batch, top=top, tokens=tokens, q=q, ua=ua, ur=ur)
+
+
+def projection_weight_bytes(ms):
+    per_layer = ms.qkv_out * ms.d_model + ms.d_model * ms.n_heads * ms.head_dim + 3 * ms.d_ffn * ms.d_model
+    return 2 * (ms.n_layers * per_layer + ms.vocab * ms.d_model)
+
+
+def run_steps(w, n_steps, sched):
+    """n_steps full steps; returns list of host results of the last step."""
+    import torch
+    from paper_2512_09963_amd import binding as gsb, workload as wl
+    db, ver, kv = w["db"], w["ver"], w["kv"]
+    last = None
+    for _ in range(n_steps):
+        wl.verify(ver, kv, db, workspace=w["ws"], want_logits=False, out=w["out"])
+        for k in ("accepted_len", "accept_stat", "next_token"):
+            w["host"][k].copy_(w["out"][k], non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        m = w["host"]["accepted_len"].numpy()
+        st = w["host"]["accept_stat"].numpy()
+        last = gsb.gs_schedule_gamma(m, st, db.gamma, sched["alpha"], sched["X"], sched["eta"], sched["beta"],
+                                     sched["C"], 0, -1)
+    return last
+
+
+def accept_leg(seed):
+    """gs_accept_reject alone: 64 servers x gamma 8 over vocab 151936, sigma = 1."""
+    import torch
+    from paper_2512_09963_amd import binding as gsb, synth
+    dev = torch.device("cuda:0")
+    N, g, V = 64, 8, 151936
+    gamma = np.full(N, g, np.int32)
+    inp = synth.accept_inputs(seed, gamma, V, 1.0)
+    R, G = N * (g + 1), N * g
+    tl0 = torch.from_numpy(inp.target_logits).to(dev)
+    q0 = torch.from_numpy(inp.q_probs).to(dev)
+    tok0 = torch.from_numpy(inp.draft_tokens).to(dev)
+    ua = torch.from_numpy(inp.u_accept).to(dev)
+    ur = torch.from_numpy(inp.u_resample).to(dev)
+    sets = []
+    for k in range(5):   # rotated copies: 5 x 0.66 GB so that no cache level serves a repeat
+        sh = 1000 * k
+        sets.append((torch.roll(tl0, sh, 1).contiguous(), torch.roll(q0, sh, 1).contiguous(),
+                     ((tok0 + sh) % V).int()))
+    cu = torch.from_numpy(synth.cu_rows_of(gamma)).to(dev)
+    out = gsb.make_accept_out(N, G, dev, want_ratio=False)
+    ws = torch.empty(gsb.gs_accept_workspace_bytes(N, R, V), dtype=torch.uint8, device=dev)
+
+    def call(k):
+        tl, q, tok = sets[k % len(sets)]
+        gsb.gs_accept_reject(gamma, cu, V, tl, q, tok, ua, ur, out, ws)
+
+    for k in range(10):
+        call(k)
+    torch.cuda.synchronize()
+    iters, n_rej = 100, 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(iters):
+        call(k)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / iters
+    n_rej = int((out["accepted_len"] < g).sum().item())
+    alg = 4.0 * V * (R + n_rej)
+    gbs = alg / us / 1e3
+    return {"workload": "accept/reject+resample, 64 servers x gamma 8, vocab 151936, fp32, sigma 1.0",
+            "us_per_call": round(us, 2), "algorithmic_bytes": alg, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "rejecting_servers": n_rej}
+
+
+def cpu_baseline(ms, w, seed):
+    """The oracle as it stands on the host cores: embed + 1 and 2 decoder layers + LM head + accept,
+    extrapolated linearly in the layer count to the full depth."""
+    import dataclasses
+    from oracle import accept_reject as ar, forward as fw
+    from paper_2512_09963_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    batch = w["batch"]
+    times = {}
+    layers = [synth.layer_weights(ms, seed, l) for l in range(2)]
+    logits = None
+    for nl in (1, 2):
+        sub = dataclasses.replace(ms, n_layers=nl)
+        cache = [(synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, 16),
+                  synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, 16)) for l in range(nl)]
+        t0 = time.time()
+        logits = fw.verify_forward(sub, w["tokens"], batch.gamma, batch.ctx_len, batch.block_table, 16, w["top"],
+                                   lambda l: layers[l], lambda l: cache[l])
+        times[nl] = time.time() - t0
+    cu = batch.cu_rows
+    d_tok = np.concatenate([w["tokens"][cu[i] + 1:cu[i + 1]] for i in range(batch.n_servers)])
+    t0 = time.time()
+    ar.accept_reject(batch.gamma, logits.astype(np.float32), w["q"], d_tok, w["ua"], w["ur"])
+    t_acc = time.time() - t0
+    per_layer = times[2] - times[1]
+    fixed = times[1] - per_layer
+    est = fixed + ms.n_layers * per_layer + t_acc
+    return {"value": round(batch.n_draft / est, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"embedding + 1 and 2 of {ms.n_layers} decoder layers + LM head + accept stage timed in full "
+                      f"({times[1]:.1f} s, {times[2]:.1f} s, accept {t_acc:.2f} s); step time extrapolated linearly "
+                      f"in the layer count to {est:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no collectives, no sharding)", file=sys.stderr)
+        sys.exit(2)
+    import dataclasses
+    import torch
+    from paper_2512_09963_amd import binding as gsb, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    gsb.lib()
+    seed = synth.MASTER_SEED
+    ms = synth.LLAMA3_8B
+    if args.layers:
+        ms = dataclasses.replace(ms, n_layers=args.layers)
+    w = build_workload(ms, seed)
+    db, ver = w["db"], w["ver"]
+    dev = torch.device("cuda:0")
+    w["ws"] = torch.empty(ver.gs_workspace_bytes(db.n_rows, db.n_servers, db.max_ctx), dtype=torch.uint8, device=dev)
+    w["out"] = gsb.make_accept_out(db.n_servers, db.n_draft, dev, want_ratio=False)
+    w["host"] = {k: torch.empty(db.n_servers, dtype=w["out"][k].dtype, pin_memory=True)
+                 for k in ("accepted_len", "accept_stat", "next_token")}
+    sched = dict(alpha=np.full(db.n_servers, 0.5), X=np.ones(db.n_servers), eta=0.2, beta=0.5, C=int(db.n_draft))
+
+    ver.gs_profile_enable(True)          # HIP events around every stage, on the launch stream
+    run_steps(w, args.warmup, sched)
+    torch.cuda.synchronize()
+    ver.gs_profile_read()
+    t0 = time.perf_counter()
+    run_steps(w, args.steps, sched)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = ver.gs_profile_read()
+    ver.gs_profile_enable(False)
+
+    ms_step = dt * 1e3 / args.steps
+    emitted = float(w["host"]["accepted_len"].sum().item() + db.n_servers)
+    gemm_ms, gemm_launches = stages["gemm"]
+    w_bytes = projection_weight_bytes(ms)
+    gemm_ms_step = gemm_ms / args.steps
+    achieved = w_bytes / (gemm_ms_step * 1e-3) / 1e9
+    res = {
+        "metric": "verified_tokens_per_s", "value": round(db.n_draft / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-8b-shaped verify (32 layers, d 4096, 32q/8kv heads, ffn 14336, vocab 128256), "
+                               "8 draft servers, gamma U[3,8], ctx 2048, 16-token KV pages",
+                   "n_servers": db.n_servers, "draft_tokens": db.n_draft, "target_rows": db.n_rows,
+                   "gamma": [int(g) for g in db.gamma]},
+        "emitted_tokens_per_s": round(emitted / (ms_step * 1e-3), 1),
+        "roofline": {"kernel": "gemm_bf16_skinny (all projections of a step)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": round(w_bytes / (gemm_launches / args.steps)),
+                     "us_per_launch": round(gemm_ms * 1e3 / gemm_launches, 2)},
+        "stage_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in stages.items()},
+    }
+    if args.layers:
+        res["invalid"] = "debug run with fewer layers"
+    if not args.skip_accept_leg:
+        res["accept_kernel"] = accept_leg(seed)
+    if not args.skip_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(ms, w, seed)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

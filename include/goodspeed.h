@@ -144,7 +144,12 @@ typedef struct {
   const float* const* norm2;  /* host [n_layers] of dev [d] fp32 (FFN pre-norm)          */
 } gs_weights;
 
-/* Paged KV cache, model dtype, layout [n_layers][n_pages][H_kv][page_size][hd]; K is stored rotated. */
+/* Paged KV cache in the model dtype.  K pages are key-major, V pages channel-major
+ * (so that the slots of one channel are contiguous, which is what the second attention
+ * product reads):
+ *   k_pages [n_layers][n_pages][H_kv][page_size][hd]   K stored rotated
+ *   v_pages [n_layers][n_pages][H_kv][hd][page_size]
+ * page_size must be a multiple of 16 for GS_BF16 models. */
 typedef struct {
   void* k_pages;
   void* v_pages;
@@ -193,6 +198,17 @@ size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int 
 gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* batch,
                           const gs_accept_out* out, float* logits_out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------- */
+/* Measurement aid (not part of the method): when enabled, gs_verify_batch      */
+/* brackets every stage with a pair of HIP events recorded on the caller's      */
+/* stream.  gs_profile_read waits for the recorded events, returns per stage    */
+/* the summed milliseconds and the number of bracketed launches since the last  */
+/* read (arrays of GS_N_STAGES, host), and clears the record.                   */
+/* ------------------------------------------------------------------------- */
+enum { GS_STAGE_GEMM = 0, GS_STAGE_ATTENTION = 1, GS_STAGE_GLUE = 2, GS_STAGE_ACCEPT = 3, GS_N_STAGES = 4 };
+gs_status gs_profile_enable(gs_ctx* ctx, int on);
+gs_status gs_profile_read(gs_ctx* ctx, double* stage_ms, long* stage_launches);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,8 @@ GS_F32, GS_BF16 = 0, 1
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_schedule_gamma",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read"]
+STAGES = ["gemm", "attention", "glue", "accept"]
 
 
 class GsError(RuntimeError):
@@ -87,6 +88,10 @@ def lib():
             L.gs_verify_batch.restype = C.c_int
             L.gs_verify_batch.argtypes = [C.c_void_p, C.POINTER(gs_kv_cache), C.POINTER(gs_batch),
                                           C.POINTER(gs_accept_out), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+            L.gs_profile_enable.restype = C.c_int
+            L.gs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+            L.gs_profile_read.restype = C.c_int
+            L.gs_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -184,6 +189,16 @@ class Verifier:
             self.close()
         except Exception:
             pass
+
+    def gs_profile_enable(self, on):
+        _check(lib().gs_profile_enable(self._ctx, 1 if on else 0))
+
+    def gs_profile_read(self):
+        """dict stage -> (milliseconds, launches) since the last read."""
+        ms = (C.c_double * len(STAGES))()
+        cnt = (C.c_long * len(STAGES))()
+        _check(lib().gs_profile_read(self._ctx, ms, cnt))
+        return {s: (ms[i], cnt[i]) for i, s in enumerate(STAGES)}
 
     def gs_workspace_bytes(self, max_rows, max_servers, max_ctx):
         return int(lib().gs_workspace_bytes(self._ctx, max_rows, max_servers, max_ctx))

@@ -41,6 +41,11 @@ struct gs_ctx {
   std::vector<const void*> wqkv, wo, wgu, wd;
   std::vector<const float*> norm1, norm2;
   size_t elem;   // bytes per stored element
+  // optional per-stage timing with HIP events on the caller's stream
+  bool profile = false;
+  std::vector<hipEvent_t> ev_start, ev_stop;
+  std::vector<int> ev_stage;
+  size_t ev_used = 0;
 };
 
 namespace {
@@ -159,9 +164,71 @@ extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, g
 }
 
 extern "C" gs_status gs_destroy(gs_ctx* ctx) {
+  if (ctx) {
+    for (hipEvent_t e : ctx->ev_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_stop) (void)hipEventDestroy(e);
+  }
   delete ctx;
   return GS_OK;
 }
+
+extern "C" gs_status gs_profile_enable(gs_ctx* ctx, int on) {
+  if (!ctx) return gs::fail(GS_EINVAL, "null ctx");
+  ctx->profile = on != 0;
+  ctx->ev_used = 0;
+  return GS_OK;
+}
+
+extern "C" gs_status gs_profile_read(gs_ctx* ctx, double* stage_ms, long* stage_launches) {
+  if (!ctx || !stage_ms || !stage_launches) return gs::fail(GS_EINVAL, "null argument");
+  for (int s = 0; s < GS_N_STAGES; ++s) {
+    stage_ms[s] = 0.0;
+    stage_launches[s] = 0;
+  }
+  for (size_t i = 0; i < ctx->ev_used; ++i) {
+    GS_HIP_CHECK(hipEventSynchronize(ctx->ev_stop[i]));
+    float ms = 0.f;
+    GS_HIP_CHECK(hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]));
+    stage_ms[ctx->ev_stage[i]] += ms;
+    stage_launches[ctx->ev_stage[i]] += 1;
+  }
+  ctx->ev_used = 0;
+  return GS_OK;
+}
+
+namespace {
+
+// Brackets the launches of one stage with a pair of events when profiling is on.
+struct StageTimer {
+  gs_ctx* ctx;
+  hipStream_t stream;
+  bool active = false;
+  StageTimer(gs_ctx* c, hipStream_t s) : ctx(c), stream(s) {}
+  gs_status begin(int stage) {
+    if (!ctx->profile) return GS_OK;
+    if (ctx->ev_used == ctx->ev_start.size()) {
+      hipEvent_t a, b;
+      GS_HIP_CHECK(hipEventCreate(&a));
+      GS_HIP_CHECK(hipEventCreate(&b));
+      ctx->ev_start.push_back(a);
+      ctx->ev_stop.push_back(b);
+      ctx->ev_stage.push_back(0);
+    }
+    ctx->ev_stage[ctx->ev_used] = stage;
+    GS_HIP_CHECK(hipEventRecord(ctx->ev_start[ctx->ev_used], stream));
+    active = true;
+    return GS_OK;
+  }
+  gs_status end() {
+    if (!active) return GS_OK;
+    GS_HIP_CHECK(hipEventRecord(ctx->ev_stop[ctx->ev_used], stream));
+    ctx->ev_used += 1;
+    active = false;
+    return GS_OK;
+  }
+};
+
+}  // namespace
 
 extern "C" size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx) {
   if (!ctx || max_rows <= 0 || max_servers <= 0 || max_ctx <= 0) return 0;
@@ -217,34 +284,41 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     if (st != GS_OK) return st; \
   } while (0)
 
-  GS_TRY(gs::launch_embed(m.dtype, ctx->embed, b->tokens, p.x, rows, d, stream));
+  StageTimer timer(ctx, stream);
+#define GS_STAGE(stage, call)   \
+  do {                          \
+    GS_TRY(timer.begin(stage)); \
+    GS_TRY(call);               \
+    GS_TRY(timer.end());        \
+  } while (0)
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(m.dtype, ctx->embed, b->tokens, p.x, rows, d, stream));
   const float* pending = nullptr;   // split-K partials of the projection whose result is still to be added to x
   int pending_splits = 0;
   for (int l = 0; l < m.n_layers; ++l) {
-    GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
-    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
     char* kl = static_cast<char*>(kv->k_pages) + layer_stride * l;
     char* vl = static_cast<char*>(kv->v_pages) + layer_stride * l;
-    GS_TRY(gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, b->cu_rows,
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, b->cu_rows,
                                   b->ctx_len, n, b->block_table, b->max_blocks, kv->page_size, m.n_heads,
                                   m.n_kv_heads, m.head_dim, m.rope_theta, p.q, kl, vl, stream));
-    GS_TRY(gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
+    GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
                                 kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_splits,
                                 p.attn_scratch, p.attn, stream));
-    GS_TRY(gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
-    GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows, ctx->norm2[l],
-                                  m.rms_eps, p.h, d, stream));
-    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
-    GS_TRY(gs::launch_swiglu(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
-    GS_TRY(gs::launch_gemm(m.dtype, p.act, ctx->wd[l], p.partial, rows, d, F, stream));
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
+                                                   ctx->norm2[l], m.rms_eps, p.h, d, stream));
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_swiglu(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.act, ctx->wd[l], p.partial, rows, d, F, stream));
     pending = p.partial;
     pending_splits = gs::gemm_splits(m.dtype, rows, d, F);
   }
-  GS_TRY(gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
   float* logits = logits_out ? logits_out : p.logits;
   const int lm_splits = gs::gemm_splits(m.dtype, rows, m.vocab, d);
   if (lm_splits == 1) {
-    GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->lm_head, logits, rows, m.vocab, d, stream));
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->lm_head, logits, rows, m.vocab, d, stream));
   } else {   // small vocabularies only: the partials fit the projection scratch
     GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->lm_head, p.partial, rows, m.vocab, d, stream));
     const size_t n_out = (size_t)rows * m.vocab;
@@ -256,9 +330,10 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
       gather_draft_tokens_kernel<<<n, 64, 0, stream>>>(b->tokens, b->cu_rows, n, p.draft_tokens);
       GS_LAUNCH_CHECK("gather_draft_tokens");
     }
-    GS_TRY(gs::launch_accept(n, rows, b->cu_rows, m.vocab, logits, b->q_probs, p.draft_tokens, b->u_accept,
-                             b->u_resample, out, p.accept_ws, stream));
+    GS_STAGE(GS_STAGE_ACCEPT, gs::launch_accept(n, rows, b->cu_rows, m.vocab, logits, b->q_probs, p.draft_tokens,
+                                                b->u_accept, b->u_resample, out, p.accept_ws, stream));
   }
+#undef GS_STAGE
 #undef GS_TRY
   return GS_OK;
 }
