@@ -5,9 +5,9 @@
 //   K pages [page][H_kv][slot][hd]   (key-major: a key's head vector is contiguous)
 //   V pages [page][H_kv][hd][slot]   (transposed: the slots of one channel are contiguous)
 //
-// bf16 path (MFMA, no LDS staging of K/V): one workgroup per (server, KV head, KV split);
-// its four waves take interleaved 32-key steps.  All T_i * G query rows that share the KV
-// head are stacked in the MFMA N dimension, so each K/V byte is read once per workgroup.
+// bf16 path (MFMA, no LDS staging of K/V): one workgroup per (server, KV head, KV split), one
+// wave per 16 of the T_i * G query rows that share the KV head (token-major, head-minor), so
+// each K/V byte leaves HBM once per workgroup and the other waves hit it in cache.
 //   S^T = K Q^T : A operand = 16 keys x 32 channels read straight from the K page (16 bytes
 //                 per lane), B operand = Q rows (kept in registers for the whole kernel).
 //   The result layout puts a query row in lane%16 and 4 consecutive keys in each lane, which
@@ -94,91 +94,107 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA path.  grid (n_splits, H_kv, N), block 256.
-// partial_o [R][H][n_splits*4... merged per workgroup -> n_splits][HD] fp32, partial_ml [R][H][n_splits][2].
+// bf16 MFMA path.  grid (n_splits, H_kv, N); one wave per 16-row query tile (blockDim = 64 *
+// tiles); the waves of a workgroup read the same K/V (served by L1/L2 after the first) and
+// never synchronise.  partial_o [R][H][n_splits][HD] fp32, partial_ml [R][H][n_splits][2].
 // ------------------------------------------------------------------------------------------
-template <int NQ, int HD, int G>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q,
-                                                        const bf16_t* __restrict__ k_pages,
-                                                        const bf16_t* __restrict__ v_pages,
-                                                        const int* __restrict__ block_table, int max_blocks,
-                                                        const int* __restrict__ cu_rows,
-                                                        const int* __restrict__ ctx_len, int page_size, int n_heads,
-                                                        int n_kv, int n_splits, int q_row_offset,
-                                                        float* __restrict__ partial_o,
-                                                        float* __restrict__ partial_ml) {
+template <int HD, int G>
+__global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict__ q,
+                                                         const bf16_t* __restrict__ k_pages,
+                                                         const bf16_t* __restrict__ v_pages,
+                                                         const int* __restrict__ block_table, int max_blocks,
+                                                         const int* __restrict__ cu_rows,
+                                                         const int* __restrict__ ctx_len, int page_size, int n_heads,
+                                                         int n_kv, int n_splits, int q_row_offset,
+                                                         float* __restrict__ partial_o,
+                                                         float* __restrict__ partial_ml) {
   constexpr int KS = HD / 32;   // k steps of the first product
   constexpr int DT = HD / 16;   // channel tiles of the second product
   const int split = blockIdx.x, kh = blockIdx.y, srv = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, c = lane & 15;
   const int row0 = cu_rows[srv];
   const int T = cu_rows[srv + 1] - row0;
   const int L = ctx_len[srv];
   const int n_keys = L + T;
-  const int rows = T * G - q_row_offset;          // query rows (token-major, head-minor) of this launch
+  const int tile_row0 = q_row_offset + wave * 16;   // first query row (token-major, head-minor) of this wave
+  const int rows = T * G - tile_row0;                // valid rows in this tile (may exceed 16)
   if (rows <= 0) return;
   const int* bt = block_table + (size_t)srv * max_blocks;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);   // scores in log2 units
 
-  // Q fragments (B operand): query row = qt*16 + c, channels ks*32 + g*8 ..
-  bf16x8_t qf[NQ][KS];
-  int tok_of_row[NQ];                    // block token index j of this lane's query row (per tile)
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    const int lr = q_row_offset + qt * 16 + c;
-    const int j = lr / G, hg = lr - j * G;
-    const bool ok = (qt * 16 + c) < rows;
-    tok_of_row[qt] = ok ? j : -1;
-    const bf16_t* src = q + ((size_t)(row0 + (ok ? j : 0)) * n_heads + kh * G + hg) * HD + g * 8;
+  // Q fragment (B operand of the first product): query row = c, channels ks*32 + g*8 ..
+  const int my_lr = tile_row0 + c;
+  const bool my_ok = c < rows;
+  const int my_j = my_ok ? my_lr / G : 0, my_hg = my_ok ? my_lr - my_j * G : 0;
+  const int limit = my_ok ? L + my_j : -1;           // last key this lane's query row may see
+  bf16x8_t qf[KS];
+  {
+    const bf16_t* src = q + ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * HD + g * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok) v = *reinterpret_cast<const uint4*>(src + ks * 32);
-      qf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(&v);
+      if (my_ok) v = *reinterpret_cast<const uint4*>(src + ks * 32);
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(&v);
     }
   }
-
-  float m_run[NQ], l_run[NQ];
-  floatx4_t oacc[NQ][DT];
+  float m_run = kNegBig, l_run = 0.f;
+  floatx4_t oacc[DT];
 #pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    m_run[qt] = kNegBig;
-    l_run[qt] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
   const int n_steps = (n_keys + 31) >> 5;
   const int per_split = (n_steps + n_splits - 1) / n_splits;
   const int step_begin = split * per_split;
-  const int step_end = min(n_steps, step_begin + per_split);
+  // a tile whose rows all belong to block tokens < j_max sees no key beyond L + j_max
+  const int j_max = min(T - 1, (tile_row0 + 15) / G);
+  const int step_end = min(min(n_steps, step_begin + per_split), ((L + j_max) >> 5) + 1);
   const int last_tile_key = ((n_keys - 1) >> 4) << 4;   // first key of the last 16-key tile that exists
 
-  for (int step = step_begin + wave; step < step_end; step += 4) {
-    // ---- S^T = K Q^T for the two 16-key tiles of this step
-    floatx4_t sacc[2][NQ];
+  auto tile_base = [&](int step, int t, int& page, int& slot0) {
+    const int key0 = min(step * 32 + t * 16, last_tile_key);   // a tile past the end re-reads the last one (masked)
+    page = bt[key0 / page_size];
+    slot0 = key0 % page_size;
+  };
+  auto load_k = [&](int page, int slot0, uint4 (&kraw)[KS]) {
+    const bf16_t* kp = k_pages + (((size_t)page * n_kv + kh) * page_size + slot0 + c) * HD + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kraw[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
+  };
+  int page_cur[2] = {0, 0}, slot_cur[2] = {0, 0};
+  uint4 k_cur[2][KS];
+  if (step_begin < step_end) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      tile_base(step_begin, t, page_cur[t], slot_cur[t]);
+      load_k(page_cur[t], slot_cur[t], k_cur[t]);
+    }
+  }
+
+  for (int step = step_begin; step < step_end; ++step) {
     uint2 vraw[2][DT];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      const int key0 = min(step * 32 + t * 16, last_tile_key);   // a tile past the end re-reads the last one (masked)
-      const int page = bt[key0 / page_size];
-      const int slot0 = key0 % page_size;
-      const bf16_t* kp = k_pages + (((size_t)page * n_kv + kh) * page_size + slot0 + c) * HD + g * 8;
-      uint4 kraw[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kraw[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
-      const bf16_t* vp = v_pages + (((size_t)page * n_kv + kh) * HD + c) * page_size + slot0 + g * 4;
+      const bf16_t* vp = v_pages + (((size_t)page_cur[t] * n_kv + kh) * HD + c) * page_size + slot_cur[t] + g * 4;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) vraw[t][dt] = *reinterpret_cast<const uint2*>(vp + (size_t)dt * 16 * page_size);
+    }
+    // first product S^T = K Q^T for the two 16-key tiles, then fetch the next step's K
+    floatx4_t sacc[2];
 #pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        floatx4_t acc = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 2; ++t) {
+      floatx4_t acc = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kraw[ks]), qf[qt][ks], acc,
-                                                        0, 0, 0);
-        sacc[t][qt] = acc;
+      for (int ks = 0; ks < KS; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&k_cur[t][ks]), qf[ks], acc, 0,
+                                                      0, 0);
+      sacc[t] = acc;
+    }
+    if (step + 1 < step_end) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        tile_base(step + 1, t, page_cur[t], slot_cur[t]);
+        load_k(page_cur[t], slot_cur[t], k_cur[t]);
       }
     }
     // keys past the end of the sequence inside the last page hold stale data: zero their V
@@ -197,121 +213,68 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
         }
       }
     }
-    // ---- mask, online softmax (per query row = lane%16, keys spread over lane groups)
-    bf16x8_t pf[NQ];
+    // mask and online softmax: the query row is lane%16, its 32 keys are spread over the 4 lane groups
+    float sv[8];
+    float mx = kNegBig;
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      const int limit = (tok_of_row[qt] >= 0) ? (L + tok_of_row[qt]) : -1;   // last visible key
-      float s[8];
-      float mx = kNegBig;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int key = step * 32 + t * 16 + g * 4 + i;
-          const float v = (key <= limit) ? sacc[t][qt][i] * scale_log2 : kNegBig;
-          s[t * 4 + i] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[qt], mx);
-      const float corr = exp2f(m_run[qt] - m_new);
-      float sum = 0.f;
-      float p[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = (s[e] > kNegBig) ? exp2f(s[e] - m_new) : 0.f;
-        sum += p[e];
-      }
-      sum += __shfl_xor(sum, 16);
-      sum += __shfl_xor(sum, 32);
-      l_run[qt] = l_run[qt] * corr + sum;
-      m_run[qt] = m_new;
-      uint4 packed;
-      packed.x = pack_bf16x2(p[0], p[1]);
-      packed.y = pack_bf16x2(p[2], p[3]);
-      packed.z = pack_bf16x2(p[4], p[5]);
-      packed.w = pack_bf16x2(p[6], p[7]);
-      pf[qt] = *reinterpret_cast<const bf16x8_t*>(&packed);
-      // rescale the output accumulators: their rows are query rows g*4 + i, whose factor sits in lane g*4 + i
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float f = __shfl(corr, g * 4 + i);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) oacc[qt][dt][i] *= f;
+        const int key = step * 32 + t * 16 + g * 4 + i;
+        const float v = (key <= limit) ? sacc[t][i] * scale_log2 : kNegBig;
+        sv[t * 4 + i] = v;
+        mx = fmaxf(mx, v);
       }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float corr = exp2f(m_run - m_new);
+    float sum = 0.f;
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = (sv[e] > kNegBig) ? exp2f(sv[e] - m_new) : 0.f;
+      sum += p[e];
     }
-    // ---- O += P V
+    sum += __shfl_xor(sum, 16);
+    sum += __shfl_xor(sum, 32);
+    l_run = l_run * corr + sum;
+    m_run = m_new;
+    uint4 packed;
+    packed.x = pack_bf16x2(p[0], p[1]);
+    packed.y = pack_bf16x2(p[2], p[3]);
+    packed.z = pack_bf16x2(p[4], p[5]);
+    packed.w = pack_bf16x2(p[6], p[7]);
+    const bf16x8_t pf = *reinterpret_cast<const bf16x8_t*>(&packed);
+    // the output accumulators hold query rows g*4 + i; their rescale factor sits in lane g*4 + i
+    float f[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __shfl(corr, g * 4 + i);
+    // second product O += P V
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      uint4 vv = make_uint4(vraw[0][dt].x, vraw[0][dt].y, vraw[1][dt].x, vraw[1][dt].y);
-      const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv);
 #pragma unroll
-      for (int qt = 0; qt < NQ; ++qt)
-        oacc[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf[qt], vf, oacc[qt][dt], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) oacc[dt][i] *= f[i];
+      uint4 vv = make_uint4(vraw[0][dt].x, vraw[0][dt].y, vraw[1][dt].x, vraw[1][dt].y);
+      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, *reinterpret_cast<const bf16x8_t*>(&vv), oacc[dt], 0, 0, 0);
     }
   }
 
-  // ---- merge the four waves through LDS (wave 0 accumulates), then write the split's partial
-  __shared__ float sh_o[NQ * 16][HD + 4];
-  __shared__ float sh_m[NQ * 16], sh_l[NQ * 16];
-  for (int w = 1; w < 4; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        if (g == 0) {
-          sh_m[qt * 16 + c] = m_run[qt];
-          sh_l[qt * 16 + c] = l_run[qt];
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) sh_o[qt * 16 + g * 4 + i][dt * 16 + c] = oacc[qt][dt][i];
-      }
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        const float m2 = sh_m[qt * 16 + c], l2 = sh_l[qt * 16 + c];
-        const float m_new = fmaxf(m_run[qt], m2);
-        const float f1 = exp2f(m_run[qt] - m_new), f2 = exp2f(m2 - m_new);
-        l_run[qt] = l_run[qt] * f1 + l2 * f2;
-        m_run[qt] = m_new;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float a1 = __shfl(f1, g * 4 + i), a2 = __shfl(f2, g * 4 + i);
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-            oacc[qt][dt][i] = oacc[qt][dt][i] * a1 + sh_o[qt * 16 + g * 4 + i][dt * 16 + c] * a2;
-        }
-      }
-    }
-    __syncthreads();
+  // this split's partial result for the tile's rows
+  if (g == 0 && my_ok) {
+    const size_t idx = ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * n_splits + split;
+    partial_ml[idx * 2 + 0] = m_run;
+    partial_ml[idx * 2 + 1] = l_run;
   }
-  if (wave == 0) {
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      // stats: lane c (g == 0) owns query row qt*16 + c
-      if (g == 0 && tok_of_row[qt] >= 0) {
-        const int lr = q_row_offset + qt * 16 + c;
-        const int j = lr / G, hg = lr - j * G;
-        const size_t idx = ((size_t)(row0 + j) * n_heads + kh * G + hg) * n_splits + split;
-        partial_ml[idx * 2 + 0] = m_run[qt];
-        partial_ml[idx * 2 + 1] = l_run[qt];
-      }
+  for (int i = 0; i < 4; ++i) {
+    const int lrow = g * 4 + i;
+    if (lrow < rows) {
+      const int lr = tile_row0 + lrow;
+      const int j = lr / G, hg = lr - j * G;
+      float* dst = partial_o + (((size_t)(row0 + j) * n_heads + kh * G + hg) * n_splits + split) * HD;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int lrow = qt * 16 + g * 4 + i;
-        if (lrow < rows) {
-          const int lr = q_row_offset + lrow;
-          const int j = lr / G, hg = lr - j * G;
-          float* dst = partial_o + (((size_t)(row0 + j) * n_heads + kh * G + hg) * n_splits + split) * HD;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) dst[dt * 16 + c] = oacc[qt][dt][i];
-        }
-      }
+      for (int dt = 0; dt < DT; ++dt) dst[dt * 16 + c] = oacc[dt][i];
     }
   }
 }
@@ -355,22 +318,13 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
                                int max_blocks, const int* cu_rows, const int* ctx_len, int n_servers, int page_size,
                                int n_heads, int n_kv, int max_block_tokens, int n_splits, float* po, float* pml,
                                hipStream_t stream) {
-  const int rows = max_block_tokens * G;
+  const int tiles = ceil_div(max_block_tokens * G, 16);
   dim3 grid(n_splits, n_kv, n_servers);
-  for (int off = 0; off < rows; off += 64) {      // at most 4 query tiles per pass
-    const int left = rows - off;
-    if (left <= 16)
-      attn_mfma_kernel<1, HD, G><<<grid, 256, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
-                                                          ctx_len, page_size, n_heads, n_kv, n_splits, off, po, pml);
-    else if (left <= 32)
-      attn_mfma_kernel<2, HD, G><<<grid, 256, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
-                                                          ctx_len, page_size, n_heads, n_kv, n_splits, off, po, pml);
-    else if (left <= 48)
-      attn_mfma_kernel<3, HD, G><<<grid, 256, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
-                                                          ctx_len, page_size, n_heads, n_kv, n_splits, off, po, pml);
-    else
-      attn_mfma_kernel<4, HD, G><<<grid, 256, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
-                                                          ctx_len, page_size, n_heads, n_kv, n_splits, off, po, pml);
+  for (int t0 = 0; t0 < tiles; t0 += 8) {      // at most 8 query tiles (waves) per workgroup
+    const int waves = tiles - t0 < 8 ? tiles - t0 : 8;
+    attn_mfma_kernel<HD, G><<<grid, 64 * waves, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
+                                                             ctx_len, page_size, n_heads, n_kv, n_splits, t0 * 16, po,
+                                                             pml);
     GS_LAUNCH_CHECK("attn_mfma");
   }
   return GS_OK;

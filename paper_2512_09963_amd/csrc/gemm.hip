@@ -7,7 +7,8 @@
 //     row per 64-wide k step straight into the MFMA B operand (no LDS hop for weights), so a
 //     wave's loads cover 16 rows x 128 contiguous bytes; DEPTH steps are kept in flight
 //   * the activations (all M rows of the k step, at most 128) are staged once per workgroup
-//     in LDS (padded rows: conflict-free 16-byte reads) and shared by the four waves
+//     in LDS (padded rows: conflict-free 16-byte reads) and shared by the four waves; their
+//     global loads run DEPTH steps ahead as well, so a step never waits on the L2 round trip
 //   * K is split across workgroups when N alone gives too few of them to fill 256 CUs; the
 //     fp32 partial sums [S][M][N] are summed by the consumer kernel, in a fixed order.
 // k order inside a step is permuted identically for both operands (lane group g takes
@@ -43,8 +44,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf
   // activation tile: MT*16 rows x 64 k = MT*128 chunks of 16 bytes
   constexpr int kChunks = MT * 128;
   constexpr int kPasses = (kChunks + kGemmThreads - 1) / kGemmThreads;
-  uint4 xreg[kPasses];
-  auto load_x = [&](int step) {
+  uint4 xreg[DEPTH][kPasses];
+  auto load_x = [&](int slot, int step) {
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
       const int ch = tid + p * kGemmThreads;
@@ -52,15 +53,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf
       uint4 v = make_uint4(0, 0, 0, 0);
       if (ch < kChunks && m0 + row < M)
         v = *reinterpret_cast<const uint4*>(X + (size_t)(m0 + row) * K + k_begin + step * kBK + col);
-      xreg[p] = v;
+      xreg[slot][p] = v;
     }
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](int buf, int slot) {
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
       const int ch = tid + p * kGemmThreads;
       const int row = ch >> 3, col = (ch & 7) * 8;
-      if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[p];
+      if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[slot][p];
     }
   };
 
@@ -78,8 +79,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf
 
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d)
-    if (d < n_steps) load_w(d, d);
-  if (n_steps > 0) load_x(0);
+    if (d < n_steps) {
+      load_w(d, d);
+      load_x(d, d);
+    }
 
   for (int base = 0; base < n_steps; base += DEPTH) {
 #pragma unroll
@@ -87,11 +90,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf
       const int step = base + d;
       if (step < n_steps) {
         const int buf = step & 1;
-        store_x(buf);
+        store_x(buf, d);
         __syncthreads();
-        if (step + 1 < n_steps) load_x(step + 1);
         const uint4 w0 = wreg[d][0], w1 = wreg[d][1];
-        if (step + DEPTH < n_steps) load_w(d, step + DEPTH);
+        if (step + DEPTH < n_steps) {
+          load_w(d, step + DEPTH);
+          load_x(d, step + DEPTH);
+        }
         const bf16x8_t b0 = *reinterpret_cast<const bf16x8_t*>(&w0);
         const bf16x8_t b1 = *reinterpret_cast<const bf16x8_t*>(&w1);
 #pragma unroll
@@ -163,8 +168,8 @@ int gemm_splits(int dtype, int M, int N, int K) {
   if (dtype != GS_BF16) return 1;
   const int n_blocks = N / 64;
   const int m_chunks = ceil_div(M, 128);
-  int want = ceil_div(768, n_blocks * m_chunks);     // about three workgroups per CU
-  int max_s = K / 512 > 0 ? K / 512 : 1;              // at least 8 steps per split
+  int want = (512 + n_blocks * m_chunks / 2) / (n_blocks * m_chunks);   // about two workgroups per CU
+  int max_s = K / 512 > 0 ? K / 512 : 1;                                // at least 8 steps per split
   int s = want < max_s ? want : max_s;
   if (s < 1) s = 1;
   const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
@@ -181,13 +186,13 @@ gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, 
     const bf16_t* w = static_cast<const bf16_t*>(W);
     const int tiles = ceil_div(M, 16);
     if (tiles <= 1) {
-      gemm_bf16_skinny_kernel<1, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+      gemm_bf16_skinny_kernel<1, 2><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
     } else if (tiles <= 2) {
-      gemm_bf16_skinny_kernel<2, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+      gemm_bf16_skinny_kernel<2, 2><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
     } else if (tiles <= 4) {
-      gemm_bf16_skinny_kernel<4, 4><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
+      gemm_bf16_skinny_kernel<4, 2><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
     } else {
-      gemm_bf16_skinny_kernel<8, 4><<<dim3(N / 64, s, ceil_div(M, 128)), kGemmThreads, 0, stream>>>(x, w, P, M, N, K,
+      gemm_bf16_skinny_kernel<8, 2><<<dim3(N / 64, s, ceil_div(M, 128)), kGemmThreads, 0, stream>>>(x, w, P, M, N, K,
                                                                                                    k_per);
     }
     GS_LAUNCH_CHECK("gemm_bf16_skinny");

@@ -8,11 +8,14 @@
 namespace gs {
 namespace {
 
-__device__ __forceinline__ float block_sum_256(float v, float* sh /*[4]*/) {
+// Sum over the workgroup (any multiple of 64 threads up to 1024), fixed order.
+__device__ __forceinline__ float block_sum(float v, float* sh /*[16]*/) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
-  float t = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+  float t = 0.f;
+  const int n_waves = blockDim.x >> 6;
+  for (int w = 0; w < n_waves; ++w) t += sh[w];
   __syncthreads();
   return t;
 }
@@ -36,39 +39,64 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ embed,
 }
 
 // x[r] += sum_s partial[s][r] (if partial), then h[r] = x[r] * w / sqrt(mean(x[r]^2) + eps).
+// One workgroup per row, one float4 per lane and pass; the loads of the S partials are
+// independent, so they are issued back to back (d % 4 == 0).
 template <typename T>
-__global__ __launch_bounds__(256) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ partial,
-                                                          int n_splits, int n_rows, const float* __restrict__ w,
-                                                          float eps, T* __restrict__ h, int d) {
-  __shared__ float sh[4];
+__global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ partial,
+                                                           int n_splits, int n_rows, const float* __restrict__ w,
+                                                           float eps, T* __restrict__ h, int d) {
+  __shared__ float sh[16];
   const int r = blockIdx.x;
-  float* xr = x + (size_t)r * d;
+  float4* xr = reinterpret_cast<float4*>(x + (size_t)r * d);
+  const int d4 = d >> 2;
+  const size_t split_stride = (size_t)n_rows * d4;
+  const float4* pr = reinterpret_cast<const float4*>(partial) + (size_t)r * d4;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = xr[i];
+  for (int i = threadIdx.x; i < d4; i += blockDim.x) {
+    float4 v = xr[i];
     if (partial) {
-      float add = 0.f;
-      for (int s = 0; s < n_splits; ++s) add += partial[((size_t)s * n_rows + r) * d + i];
-      v += add;
+      float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0;
+      int s = 0;
+      for (; s + 4 <= n_splits; s += 4) {
+        const float4 p0 = pr[(size_t)s * split_stride + i], p1 = pr[(size_t)(s + 1) * split_stride + i];
+        const float4 p2 = pr[(size_t)(s + 2) * split_stride + i], p3 = pr[(size_t)(s + 3) * split_stride + i];
+        a0.x += p0.x + p1.x; a0.y += p0.y + p1.y; a0.z += p0.z + p1.z; a0.w += p0.w + p1.w;
+        a1.x += p2.x + p3.x; a1.y += p2.y + p3.y; a1.z += p2.z + p3.z; a1.w += p2.w + p3.w;
+      }
+      for (; s < n_splits; ++s) {
+        const float4 p0 = pr[(size_t)s * split_stride + i];
+        a0.x += p0.x; a0.y += p0.y; a0.z += p0.z; a0.w += p0.w;
+      }
+      v.x += a0.x + a1.x; v.y += a0.y + a1.y; v.z += a0.z + a1.z; v.w += a0.w + a1.w;
       xr[i] = v;
     }
-    ss += v * v;
+    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
-  const float tot = block_sum_256(ss, sh);
+  const float tot = block_sum(ss, sh);
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) Storage<T>::store(h + (size_t)r * d + i, xr[i] * inv * w[i]);
+  const float4* wr = reinterpret_cast<const float4*>(w);
+  for (int i = threadIdx.x; i < d4; i += blockDim.x) {
+    const float4 v = xr[i], ww = wr[i];
+    T* dst = h + (size_t)r * d + 4 * i;
+    Storage<T>::store(dst + 0, v.x * inv * ww.x);
+    Storage<T>::store(dst + 1, v.y * inv * ww.y);
+    Storage<T>::store(dst + 2, v.z * inv * ww.z);
+    Storage<T>::store(dst + 3, v.w * inv * ww.w);
+  }
 }
 
 // Sums the QKV partials, rotates Q and K at the row's position, stores Q [R][H][hd] and
 // appends K ([page][H_kv][slot][hd]) and V ([page][H_kv][hd][slot]) to the layer's pages.
+// One workgroup per row; a lane owns one rotation pair index i for several heads, so the
+// angle's sine and cosine are computed once per lane.  blockDim.x is a multiple of hd/2.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
-                                                          const int* __restrict__ cu_rows,
-                                                          const int* __restrict__ ctx_len, int n_servers,
-                                                          const int* __restrict__ block_table, int max_blocks,
-                                                          int page_size, int n_heads, int n_kv, int hd,
-                                                          float log2_theta, T* __restrict__ q_out,
-                                                          T* __restrict__ k_pages, T* __restrict__ v_pages) {
+__global__ __launch_bounds__(1024) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
+                                                           const int* __restrict__ cu_rows,
+                                                           const int* __restrict__ ctx_len, int n_servers,
+                                                           const int* __restrict__ block_table, int max_blocks,
+                                                           int page_size, int n_heads, int n_kv, int hd,
+                                                           float log2_theta, T* __restrict__ q_out,
+                                                           T* __restrict__ k_pages, T* __restrict__ v_pages) {
   const int r = blockIdx.x;
   const int srv = server_of_row(cu_rows, n_servers, r);
   const int pos = ctx_len[srv] + (r - cu_rows[srv]);
@@ -76,33 +104,32 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   const int slot = pos % page_size;
   const int width = (n_heads + 2 * n_kv) * hd;
   const int half = hd >> 1;
+  const size_t split_stride = (size_t)n_rows * width;
+  const float* row = qkv + (size_t)r * width;
   auto value = [&](int col) {
-    float v = 0.f;
-    for (int s = 0; s < n_splits; ++s) v += qkv[((size_t)s * n_rows + r) * width + col];
-    return v;
+    float v0 = 0.f, v1 = 0.f;
+    int s = 0;
+    for (; s + 2 <= n_splits; s += 2) {
+      v0 += row[(size_t)s * split_stride + col];
+      v1 += row[(size_t)(s + 1) * split_stride + col];
+    }
+    if (s < n_splits) v0 += row[(size_t)s * split_stride + col];
+    return v0 + v1;
   };
-  // rotated heads: Q heads then K heads, one (i, i + hd/2) pair per work item
-  const int n_rot = (n_heads + n_kv) * half;
-  for (int e = threadIdx.x; e < n_rot; e += 256) {
-    const int head = e / half, i = e - head * half;
-    const float inv_freq = exp2f(-2.0f * (float)i / (float)hd * log2_theta);
-    float sn, cs;
-    sincosf((float)pos * inv_freq, &sn, &cs);
+  const int i = threadIdx.x % half, grp = threadIdx.x / half, n_grp = blockDim.x / half;
+  const float inv_freq = exp2f(-2.0f * (float)i / (float)hd * log2_theta);
+  float sn, cs;
+  sincosf((float)pos * inv_freq, &sn, &cs);
+  for (int head = grp; head < n_heads + n_kv; head += n_grp) {
     const float a = value(head * hd + i), b = value(head * hd + i + half);
     const float ra = a * cs - b * sn, rb = b * cs + a * sn;
-    if (head < n_heads) {
-      T* dst = q_out + ((size_t)r * n_heads + head) * hd;
-      Storage<T>::store(dst + i, ra);
-      Storage<T>::store(dst + i + half, rb);
-    } else {
-      const int kh = head - n_heads;
-      T* dst = k_pages + (((size_t)page * n_kv + kh) * page_size + slot) * hd;
-      Storage<T>::store(dst + i, ra);
-      Storage<T>::store(dst + i + half, rb);
-    }
+    T* dst = (head < n_heads) ? q_out + ((size_t)r * n_heads + head) * hd
+                              : k_pages + (((size_t)page * n_kv + (head - n_heads)) * page_size + slot) * hd;
+    Storage<T>::store(dst + i, ra);
+    Storage<T>::store(dst + i + half, rb);
   }
   const int v_col0 = (n_heads + n_kv) * hd;
-  for (int e = threadIdx.x; e < n_kv * hd; e += 256) {
+  for (int e = threadIdx.x; e < n_kv * hd; e += blockDim.x) {
     const int kh = e / hd, dd = e - kh * hd;
     Storage<T>::store(v_pages + (((size_t)page * n_kv + kh) * hd + dd) * page_size + slot, value(v_col0 + e));
   }
@@ -144,8 +171,10 @@ gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x
 
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
                              float eps, void* h, int d, hipStream_t stream) {
-  GS_DISPATCH_T(dtype, add_rmsnorm_kernel<T><<<n_rows, 256, 0, stream>>>(x, partial, n_splits, n_rows, w, eps,
-                                                                        static_cast<T*>(h), d);)
+  int threads = ceil_div(d / 4, 64) * 64;
+  if (threads > 1024) threads = 1024;
+  GS_DISPATCH_T(dtype, add_rmsnorm_kernel<T><<<n_rows, threads, 0, stream>>>(x, partial, n_splits, n_rows, w, eps,
+                                                                            static_cast<T*>(h), d);)
   GS_LAUNCH_CHECK("add_rmsnorm");
   return GS_OK;
 }
@@ -155,7 +184,10 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream) {
   const float log2_theta = log2f(rope_theta);
-  GS_DISPATCH_T(dtype, rope_append_kernel<T><<<n_rows, 256, 0, stream>>>(
+  const int half = hd / 2;
+  int groups = (n_heads + n_kv) < 1024 / half ? (n_heads + n_kv) : 1024 / half;
+  const int threads = ceil_div(groups * half, 64) * 64 / half * half;   // multiple of 64 and of hd/2 (hd is 64 or 128)
+  GS_DISPATCH_T(dtype, rope_append_kernel<T><<<n_rows, threads, 0, stream>>>(
                            qkv, n_splits, n_rows, cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size,
                            n_heads, n_kv, hd, log2_theta, static_cast<T*>(q_out), static_cast<T*>(k_pages),
                            static_cast<T*>(v_pages));)

@@ -130,6 +130,7 @@ extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, g
   if (m.n_layers <= 0 || m.d_model <= 0 || m.n_heads <= 0 || m.n_kv_heads <= 0 || m.head_dim <= 0 || m.d_ffn <= 0 ||
       m.vocab <= 0)
     return gs::fail(GS_EINVAL, "model dimensions must be positive");
+  if (m.d_model % 4) return gs::fail(GS_ESHAPE, "d_model must be a multiple of 4");
   if (m.dtype != GS_F32 && m.dtype != GS_BF16) return gs::fail(GS_EINVAL, "dtype must be GS_F32 or GS_BF16");
   if (m.head_dim != 64 && m.head_dim != 128) return gs::fail(GS_ESHAPE, "head_dim must be 64 or 128");
   if (m.n_heads % m.n_kv_heads != 0) return gs::fail(GS_ESHAPE, "n_heads must be a multiple of n_kv_heads");
