@@ -37,22 +37,13 @@ def parse():
 def build_workload(ms, seed):
     import torch
     from paper_2512_09963_amd import synth, workload as wl
-    n = 8
-    gamma = synth.uniform_int(seed, ("cfg3", "gamma"), 3, 8, n)
-    ctx = np.full(n, 2048, np.int32)
-    batch = synth.make_batch(seed, gamma, ctx, 16, permute_pages=False)
-    tokens, q, ua, ur = synth.verify_side_inputs(seed, ms.vocab, gamma, sigma=0.5, tag="cfg3")
+    cfg = synth.config3(seed, ms)
     t0 = time.time()
-    top = synth.top_weights(ms, seed)
-    ver = wl.upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l))
-    kv = wl.KVCache(ms, batch.n_pages, 16, zero=False)
-    for l in range(ms.n_layers):
-        kv.set_layer(l, synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, 16),
-                     synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, 16))
+    ver, kv, db = wl.upload_config(cfg)
     torch.cuda.synchronize()
     print(f"[bench] weights + KV generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
-    db = wl.DeviceBatch(batch, tokens, q, ua, ur)
-    return dict(ver=ver, kv=kv, db=db, batch=batch, top=top, tokens=tokens, q=q, ua=ua, ur=ur)
+    return dict(ver=ver, kv=kv, db=db, batch=cfg.batch, tokens=cfg.tokens, q=cfg.q_probs, ua=cfg.u_accept,
+                ur=cfg.u_resample)
 
 
 def projection_weight_bytes(ms):
@@ -137,14 +128,16 @@ def cpu_baseline(ms, w, seed):
         cores = len(os.sched_getaffinity(0))
     batch = w["batch"]
     times = {}
-    layers = [synth.layer_weights(ms, seed, l) for l in range(2)]
+    n_sample = 8      # decoder layers timed; enough for some tens of seconds of host work
+    layers = [synth.layer_weights(ms, seed, l) for l in range(n_sample)]
+    top = synth.top_weights(ms, seed)
     logits = None
-    for nl in (1, 2):
+    for nl in (n_sample // 2, n_sample):
         sub = dataclasses.replace(ms, n_layers=nl)
         cache = [(synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, 16),
                   synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, 16)) for l in range(nl)]
         t0 = time.time()
-        logits = fw.verify_forward(sub, w["tokens"], batch.gamma, batch.ctx_len, batch.block_table, 16, w["top"],
+        logits = fw.verify_forward(sub, w["tokens"], batch.gamma, batch.ctx_len, batch.block_table, 16, top,
                                    lambda l: layers[l], lambda l: cache[l])
         times[nl] = time.time() - t0
     cu = batch.cu_rows
@@ -152,12 +145,13 @@ def cpu_baseline(ms, w, seed):
     t0 = time.time()
     ar.accept_reject(batch.gamma, logits.astype(np.float32), w["q"], d_tok, w["ua"], w["ur"])
     t_acc = time.time() - t0
-    per_layer = times[2] - times[1]
-    fixed = times[1] - per_layer
+    per_layer = (times[n_sample] - times[n_sample // 2]) / (n_sample - n_sample // 2)
+    fixed = times[n_sample] - n_sample * per_layer
     est = fixed + ms.n_layers * per_layer + t_acc
     return {"value": round(batch.n_draft / est, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"embedding + 1 and 2 of {ms.n_layers} decoder layers + LM head + accept stage timed in full "
-                      f"({times[1]:.1f} s, {times[2]:.1f} s, accept {t_acc:.2f} s); step time extrapolated linearly "
+            "sample": f"embedding + {n_sample // 2} and {n_sample} of {ms.n_layers} decoder layers + LM head + accept "
+                      f"stage timed in full ({times[n_sample // 2]:.1f} s, {times[n_sample]:.1f} s, accept "
+                      f"{t_acc:.2f} s); step time extrapolated linearly "
                       f"in the layer count to {est:.1f} s"}
 
 

@@ -89,58 +89,80 @@ def attention_server(q, k_all, v_all, ctx_len, n_heads, n_kv_heads):
     return out
 
 
+def _row_offsets(gamma):
+    gamma = np.asarray(gamma, dtype=np.int64)
+    cu = np.zeros(gamma.size + 1, dtype=np.int64)
+    cu[1:] = np.cumsum(gamma + 1)
+    return gamma, cu
+
+
+def embed_rows(top, tokens):
+    """Residual stream entering the first layer: the embedding rows of the block tokens."""
+    return np.asarray(top["embed"], dtype=np.float32)[np.asarray(tokens, dtype=np.int64)].astype(np.float64)
+
+
+def layer_forward(ms, x, W, k_pages, v_pages, gamma, ctx_len, block_table, page_size):
+    """One decoder layer on the residual stream x [R, d]; appends the block's K/V to the pages in place.
+
+    W: dict(wqkv [(H+2H_kv)hd, d], wo [d, H hd], wgu [2F, d], wd [d, F], norm1, norm2);
+    k_pages, v_pages [n_pages, H_kv, page, hd], written at positions ctx_len_i .. ctx_len_i + gamma_i.
+    """
+    gamma, cu = _row_offsets(gamma)
+    n = gamma.size
+    H, Hk, hd, F = ms.n_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn
+    R = int(cu[-1])
+    h = _store(rmsnorm(x, np.asarray(W["norm1"], dtype=np.float64), ms.rms_eps), ms.dtype)
+    qkv = h @ np.asarray(W["wqkv"], dtype=np.float64).T
+    attn = np.zeros((R, H * hd), dtype=np.float64)
+    for i in range(n):
+        T = int(gamma[i]) + 1
+        L = int(ctx_len[i])
+        rows = qkv[cu[i]:cu[i + 1]]
+        q = rows[:, : H * hd].reshape(T, H, hd).copy()
+        k = rows[:, H * hd:(H + Hk) * hd].reshape(T, Hk, hd).copy()
+        v = rows[:, (H + Hk) * hd:].reshape(T, Hk, hd)
+        for j in range(T):
+            q[j] = rope(q[j], L + j, ms.rope_theta)
+            k[j] = rope(k[j], L + j, ms.rope_theta)
+        q = _store(q, ms.dtype)
+        k = _store(k, ms.dtype)
+        v = _store(v, ms.dtype)
+        for j in range(T):
+            pos = L + j
+            pg = int(block_table[i][pos // page_size])
+            k_pages[pg, :, pos % page_size, :] = k[j]
+            v_pages[pg, :, pos % page_size, :] = v[j]
+        k_all = gather_kv(k_pages, block_table[i], L + T, page_size)
+        v_all = gather_kv(v_pages, block_table[i], L + T, page_size)
+        o = attention_server(q, k_all, v_all, L, H, Hk)
+        attn[cu[i]:cu[i + 1]] = o.reshape(T, H * hd)
+    attn = _store(attn, ms.dtype)
+    x = x + attn @ np.asarray(W["wo"], dtype=np.float64).T
+    h = _store(rmsnorm(x, np.asarray(W["norm2"], dtype=np.float64), ms.rms_eps), ms.dtype)
+    gu = h @ np.asarray(W["wgu"], dtype=np.float64).T
+    act = _store(silu(gu[:, :F]) * gu[:, F:], ms.dtype)
+    return x + act @ np.asarray(W["wd"], dtype=np.float64).T
+
+
+def lm_head(ms, x, top):
+    """Logits of the final residual stream: final RMSNorm, then the LM-head projection."""
+    h = _store(rmsnorm(x, np.asarray(top["final_norm"], dtype=np.float64), ms.rms_eps), ms.dtype)
+    return h @ np.asarray(top["lm_head"], dtype=np.float64).T
+
+
 def verify_forward(ms, tokens, gamma, ctx_len, block_table, page_size, top, get_layer, get_kv):
     """Logits [R, V] of every row of the ragged batch; appends the block's K/V to the cache.
 
     ms: object with n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab,
         rope_theta, rms_eps, dtype.
     top: dict(embed [V, d], lm_head [V, d], final_norm [d]).
-    get_layer(l): dict(wqkv [(H+2H_kv)hd, d], wo [d, H hd], wgu [2F, d], wd [d, F], norm1, norm2).
+    get_layer(l): the layer's weight dict (see layer_forward).
     get_kv(l): (k_pages, v_pages) arrays [n_pages, H_kv, page, hd], written in place at
         positions ctx_len_i .. ctx_len_i + gamma_i of each server.
     """
-    gamma = np.asarray(gamma, dtype=np.int64)
-    n = gamma.size
-    H, Hk, hd, F = ms.n_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn
-    cu = np.zeros(n + 1, dtype=np.int64)
-    cu[1:] = np.cumsum(gamma + 1)
-    R = int(cu[-1])
-    x = np.asarray(top["embed"], dtype=np.float32)[np.asarray(tokens[:R], dtype=np.int64)].astype(np.float64)
-
+    _, cu = _row_offsets(gamma)
+    x = embed_rows(top, tokens[: int(cu[-1])])
     for l in range(ms.n_layers):
-        W = get_layer(l)
         k_pages, v_pages = get_kv(l)
-        h = _store(rmsnorm(x, np.asarray(W["norm1"], dtype=np.float64), ms.rms_eps), ms.dtype)
-        qkv = h @ np.asarray(W["wqkv"], dtype=np.float64).T
-        attn = np.zeros((R, H * hd), dtype=np.float64)
-        for i in range(n):
-            T = int(gamma[i]) + 1
-            L = int(ctx_len[i])
-            rows = qkv[cu[i]:cu[i + 1]]
-            q = rows[:, : H * hd].reshape(T, H, hd).copy()
-            k = rows[:, H * hd:(H + Hk) * hd].reshape(T, Hk, hd).copy()
-            v = rows[:, (H + Hk) * hd:].reshape(T, Hk, hd)
-            for j in range(T):
-                q[j] = rope(q[j], L + j, ms.rope_theta)
-                k[j] = rope(k[j], L + j, ms.rope_theta)
-            q = _store(q, ms.dtype)
-            k = _store(k, ms.dtype)
-            v = _store(v, ms.dtype)
-            for j in range(T):
-                pos = L + j
-                pg = int(block_table[i][pos // page_size])
-                k_pages[pg, :, pos % page_size, :] = k[j]
-                v_pages[pg, :, pos % page_size, :] = v[j]
-            k_all = gather_kv(k_pages, block_table[i], L + T, page_size)
-            v_all = gather_kv(v_pages, block_table[i], L + T, page_size)
-            o = attention_server(q, k_all, v_all, L, H, Hk)
-            attn[cu[i]:cu[i + 1]] = o.reshape(T, H * hd)
-        attn = _store(attn, ms.dtype)
-        x = x + attn @ np.asarray(W["wo"], dtype=np.float64).T
-        h = _store(rmsnorm(x, np.asarray(W["norm2"], dtype=np.float64), ms.rms_eps), ms.dtype)
-        gu = h @ np.asarray(W["wgu"], dtype=np.float64).T
-        act = _store(silu(gu[:, :F]) * gu[:, F:], ms.dtype)
-        x = x + act @ np.asarray(W["wd"], dtype=np.float64).T
-
-    h = _store(rmsnorm(x, np.asarray(top["final_norm"], dtype=np.float64), ms.rms_eps), ms.dtype)
-    return h @ np.asarray(top["lm_head"], dtype=np.float64).T
+        x = layer_forward(ms, x, get_layer(l), k_pages, v_pages, gamma, ctx_len, block_table, page_size)
+    return lm_head(ms, x, top)

@@ -21,7 +21,7 @@ GS_F32, GS_BF16 = 0, 1
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_schedule_gamma",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -90,6 +90,8 @@ def lib():
                                           C.POINTER(gs_accept_out), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
             L.gs_profile_enable.restype = C.c_int
             L.gs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+            L.gs_trace_residual.restype = C.c_int
+            L.gs_trace_residual.argtypes = [C.c_void_p, C.c_void_p]
             L.gs_profile_read.restype = C.c_int
             L.gs_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -189,6 +191,11 @@ class Verifier:
             self.close()
         except Exception:
             pass
+
+    def gs_trace_residual(self, trace):
+        """trace: float32 device tensor [(n_layers + 1), R, d_model] or None."""
+        self._trace = trace
+        _check(lib().gs_trace_residual(self._ctx, _ptr(trace)))
 
     def gs_profile_enable(self, on):
         _check(lib().gs_profile_enable(self._ctx, 1 if on else 0))

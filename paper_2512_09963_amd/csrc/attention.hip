@@ -240,12 +240,22 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     sum += __shfl_xor(sum, 32);
     l_run = l_run * corr + sum;
     m_run = m_new;
-    uint4 packed;
+    // P enters the second product as a sum of two bf16 terms (value and rounding remainder), so
+    // the product sees 16 mantissa bits of P instead of 8
+    float plo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) plo[e] = p[e] - bf16_to_float(float_to_bf16(p[e]));
+    uint4 packed, packed_lo;
     packed.x = pack_bf16x2(p[0], p[1]);
     packed.y = pack_bf16x2(p[2], p[3]);
     packed.z = pack_bf16x2(p[4], p[5]);
     packed.w = pack_bf16x2(p[6], p[7]);
+    packed_lo.x = pack_bf16x2(plo[0], plo[1]);
+    packed_lo.y = pack_bf16x2(plo[2], plo[3]);
+    packed_lo.z = pack_bf16x2(plo[4], plo[5]);
+    packed_lo.w = pack_bf16x2(plo[6], plo[7]);
     const bf16x8_t pf = *reinterpret_cast<const bf16x8_t*>(&packed);
+    const bf16x8_t pf_lo = *reinterpret_cast<const bf16x8_t*>(&packed_lo);
     // the output accumulators hold query rows g*4 + i; their rescale factor sits in lane g*4 + i
     float f[4];
 #pragma unroll
@@ -256,7 +266,9 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int i = 0; i < 4; ++i) oacc[dt][i] *= f[i];
       uint4 vv = make_uint4(vraw[0][dt].x, vraw[0][dt].y, vraw[1][dt].x, vraw[1][dt].y);
-      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, *reinterpret_cast<const bf16x8_t*>(&vv), oacc[dt], 0, 0, 0);
+      const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv);
+      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, vf, oacc[dt], 0, 0, 0);
+      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_lo, vf, oacc[dt], 0, 0, 0);
     }
   }
 

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(1024) void rope_append_kernel(const float* __restri
                                                            const int* __restrict__ ctx_len, int n_servers,
                                                            const int* __restrict__ block_table, int max_blocks,
                                                            int page_size, int n_heads, int n_kv, int hd,
-                                                           float log2_theta, T* __restrict__ q_out,
+                                                           double log2_theta, T* __restrict__ q_out,
                                                            T* __restrict__ k_pages, T* __restrict__ v_pages) {
   const int r = blockIdx.x;
   const int srv = server_of_row(cu_rows, n_servers, r);
@@ -117,9 +117,12 @@ __global__ __launch_bounds__(1024) void rope_append_kernel(const float* __restri
     return v0 + v1;
   };
   const int i = threadIdx.x % half, grp = threadIdx.x / half, n_grp = blockDim.x / half;
-  const float inv_freq = exp2f(-2.0f * (float)i / (float)hd * log2_theta);
-  float sn, cs;
-  sincosf((float)pos * inv_freq, &sn, &cs);
+  // the angle pos * theta^(-2i/hd) reaches thousands of radians: form it in double, so that the
+  // rotated values agree with a float64 evaluation to fp32 rounding (once per lane, not per element)
+  const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
+  double sn_d, cs_d;
+  sincos((double)pos * inv_freq, &sn_d, &cs_d);
+  const float sn = (float)sn_d, cs = (float)cs_d;
   for (int head = grp; head < n_heads + n_kv; head += n_grp) {
     const float a = value(head * hd + i), b = value(head * hd + i + half);
     const float ra = a * cs - b * sn, rb = b * cs + a * sn;
@@ -183,7 +186,7 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              const int* ctx_len, int n_servers, const int* block_table, int max_blocks,
                              int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream) {
-  const float log2_theta = log2f(rope_theta);
+  const double log2_theta = log2((double)rope_theta);
   const int half = hd / 2;
   int groups = (n_heads + n_kv) < 1024 / half ? (n_heads + n_kv) : 1024 / half;
   const int threads = ceil_div(groups * half, 64) * 64 / half * half;   // multiple of 64 and of hd/2 (hd is 64 or 128)

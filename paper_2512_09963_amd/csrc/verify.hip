@@ -41,6 +41,7 @@ struct gs_ctx {
   std::vector<const void*> wqkv, wo, wgu, wd;
   std::vector<const float*> norm1, norm2;
   size_t elem;   // bytes per stored element
+  float* residual_trace = nullptr;   // optional: copies of the residual stream, see gs_trace_residual
   // optional per-stage timing with HIP events on the caller's stream
   bool profile = false;
   std::vector<hipEvent_t> ev_start, ev_stop;
@@ -173,6 +174,12 @@ extern "C" gs_status gs_destroy(gs_ctx* ctx) {
   return GS_OK;
 }
 
+extern "C" gs_status gs_trace_residual(gs_ctx* ctx, float* trace) {
+  if (!ctx) return gs::fail(GS_EINVAL, "null ctx");
+  ctx->residual_trace = trace;
+  return GS_OK;
+}
+
 extern "C" gs_status gs_profile_enable(gs_ctx* ctx, int on) {
   if (!ctx) return gs::fail(GS_EINVAL, "null ctx");
   ctx->profile = on != 0;
@@ -297,6 +304,9 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   int pending_splits = 0;
   for (int l = 0; l < m.n_layers; ++l) {
     GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
+    if (ctx->residual_trace)   // residual stream entering layer l (complete once the pending partials are added)
+      GS_HIP_CHECK(hipMemcpyAsync(ctx->residual_trace + (size_t)l * rows * d, p.x, sizeof(float) * rows * d,
+                                  hipMemcpyDeviceToDevice, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
     char* kl = static_cast<char*>(kv->k_pages) + layer_stride * l;
     char* vl = static_cast<char*>(kv->v_pages) + layer_stride * l;
@@ -316,6 +326,9 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     pending_splits = gs::gemm_splits(m.dtype, rows, d, F);
   }
   GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
+  if (ctx->residual_trace)
+    GS_HIP_CHECK(hipMemcpyAsync(ctx->residual_trace + (size_t)m.n_layers * rows * d, p.x, sizeof(float) * rows * d,
+                                hipMemcpyDeviceToDevice, stream));
   float* logits = logits_out ? logits_out : p.logits;
   const int lm_splits = gs::gemm_splits(m.dtype, rows, m.vocab, d);
   if (lm_splits == 1) {

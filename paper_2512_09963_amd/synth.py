@@ -355,3 +355,56 @@ def verify_side_inputs(seed, ms_vocab, gamma, sigma=0.5, logit_scale=1.0, tag="v
         tokens[cu_r[i]] = pending[i]
         tokens[cu_r[i] + 1 : cu_r[i + 1]] = d_tok[cu_d[i] : cu_d[i + 1]]
     return tokens, q, uniform01_f32(seed, (tag, "u_acc"), G), uniform01_f32(seed, (tag, "u_res"), n)
+
+
+# ----------------------------------------------------------------------------
+# The named verify configurations (shapes and distributions only)
+# ----------------------------------------------------------------------------
+
+@dataclass
+class VerifyConfig:
+    name: str
+    ms: ModelShape
+    batch: BatchShape
+    tokens: np.ndarray
+    q_probs: np.ndarray
+    u_accept: np.ndarray
+    u_resample: np.ndarray
+    seed: int
+
+
+def _verify_config(name, ms, seed, gamma, ctx, permute, sigma, logit_scale):
+    batch = make_batch(seed, gamma, ctx, 16, headroom=0, permute_pages=permute, tag=name)
+    tokens, q, ua, ur = verify_side_inputs(seed, ms.vocab, gamma, sigma=sigma, logit_scale=logit_scale, tag=name)
+    return VerifyConfig(name, ms, batch, tokens, q, ua, ur, seed)
+
+
+def config3(seed=MASTER_SEED, ms=LLAMA3_8B):
+    """8B-shaped verify: 8 servers, gamma uniform in [3, 8], 2048 cached tokens each, contiguous 16-token pages."""
+    gamma = uniform_int(seed, ("cfg3", "gamma"), 3, 8, 8)
+    return _verify_config("cfg3", ms, seed, gamma, np.full(8, 2048, np.int32), False, 0.5, 1.0)
+
+
+def config4(seed=MASTER_SEED, ms=LLAMA3_8B, headroom=64):
+    """8B-shaped ragged verify: 32 servers, gamma uniform in [1, 16], context log-uniform in [512, 8192],
+    permuted 16-token pages with room for `headroom` more tokens per server (later rounds)."""
+    gamma = uniform_int(seed, ("cfg4", "gamma"), 1, 16, 32)
+    ctx = log_uniform_int(seed, ("cfg4", "ctx"), 512, 8192, 32)
+    batch = make_batch(seed, np.full(32, 16, np.int32), ctx, 16, headroom=headroom, permute_pages=True, tag="cfg4")
+    batch = BatchShape(gamma, ctx, 16, batch.block_table, batch.n_pages)
+    tokens, q, ua, ur = verify_side_inputs(seed, ms.vocab, gamma, sigma=0.5, tag="cfg4")
+    return VerifyConfig("cfg4", ms, batch, tokens, q, ua, ur, seed)
+
+
+def config5(seed=MASTER_SEED, ms=LLAMA3_70B):
+    """70B-shaped verify: 16 servers, gamma uniform in [2, 8], 4096 cached tokens each; draft logits are
+    2 * N(0,1), independent of the target."""
+    gamma = uniform_int(seed, ("cfg5", "gamma"), 2, 8, 16)
+    return _verify_config("cfg5", ms, seed, gamma, np.full(16, 4096, np.int32), False, 0.0, 2.0)
+
+
+def draft_tokens_of(cfg_tokens, gamma):
+    """The draft tokens (without the pending tokens) in draft-row order."""
+    cu = cu_rows_of(gamma)
+    parts = [cfg_tokens[cu[i] + 1:cu[i + 1]] for i in range(len(gamma))]
+    return np.concatenate(parts) if parts else np.zeros(0, np.int32)

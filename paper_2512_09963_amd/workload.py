@@ -93,3 +93,18 @@ def verify(ver: gsb.Verifier, kv: KVCache, db: DeviceBatch, workspace=None, want
                         db.tokens, db.block_table, db.q_probs, db.u_accept, db.u_resample, out, logits, workspace,
                         stream)
     return out, logits, workspace
+
+
+def upload_config(cfg: synth.VerifyConfig, ver=None):
+    """Device side of a synth.VerifyConfig: model (random init from the seed), synthetic KV, batch."""
+    ms, seed, batch = cfg.ms, cfg.seed, cfg.batch
+    if ver is None:
+        top = synth.top_weights(ms, seed)
+        ver = upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l))
+        del top
+    kv = KVCache(ms, batch.n_pages, batch.page_size, zero=False)
+    for l in range(ms.n_layers):
+        kv.set_layer(l, synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, batch.page_size),
+                     synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, batch.page_size))
+    db = DeviceBatch(batch, cfg.tokens, cfg.q_probs, cfg.u_accept, cfg.u_resample)
+    return ver, kv, db
