@@ -2,17 +2,18 @@
 // test, and the residual / bonus draw (paper Section II-A-2; the per-server
 // statistic is the sum inside the acceptance-rate update of Section III-C).
 //
-// Four launches on one stream, no host synchronisation:
-//   row_stats      every target row is read once; each workgroup reduces one chunk of
-//                  one row to an online-softmax pair (max, sum exp(l - max))
-//   decide         one wavefront per server: merges the chunk pairs of its rows, gathers
-//                  p_j(s_j) and q_j(s_j), takes the accept decisions, finds m and the statistic
-//   residual_tiles one workgroup per 2048-token tile of the single row each server draws
-//                  from: sum of max(0, p - q) (or of p for the bonus draw)
-//   pick_token     one workgroup per server: locates the tile, then the token, whose running
-//                  sum first exceeds u * total
-// Bandwidth-bound: row_stats streams 4*V bytes per target row with 16-byte loads and keeps
-// four loads per lane in flight; everything else touches O(N*V) bytes.
+// Three launches on one stream, no host synchronisation:
+//   row_stats   every target row is read once, with non-temporal 16-byte loads, four per lane
+//               in flight; each workgroup reduces one chunk of one row to an online-softmax
+//               pair (max, sum exp(l - max))
+//   draw_tiles  grid (tile groups, servers).  Every workgroup first repeats its server's
+//               decision (merge the chunk pairs of its rows, gather p_j(s_j) and q_j(s_j),
+//               accept tests, m, statistic: a few hundred bytes out of L2), then sums
+//               max(0, p - q) (or p for the bonus draw) over its 2048-token tiles of the one
+//               row the extra token is drawn from
+//   pick_token  one workgroup per server: scans the tile sums, then the one tile, for the
+//               token whose running sum first exceeds u * total
+// Bandwidth-bound: row_stats streams 4*V bytes per target row; the draw touches O(N*V) bytes.
 #include "common.h"
 #include <cmath>
 
@@ -41,6 +42,13 @@ __device__ __forceinline__ void merge_pair(float& m, float& s, float m2, float s
 
 __device__ __forceinline__ float max4(const float4& v) { return fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)); }
 
+// 16-byte load that does not displace cache lines (the logits are read once)
+typedef float __attribute__((ext_vector_type(4))) float4_vec;
+__device__ __forceinline__ float4 stream_load4(const float4* p) {
+  const float4_vec v = __builtin_nontemporal_load(reinterpret_cast<const float4_vec*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // ---------------------------------------------------------------------------------------
 // row_stats: grid (chunks, rows).  VEC: rows are 16-byte aligned and V % 4 == 0.
 // ---------------------------------------------------------------------------------------
@@ -58,10 +66,10 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* _
     const float4* p = reinterpret_cast<const float4*>(base + begin);
     const int n4 = (end - begin) >> 2;
     for (int i = threadIdx.x; i < n4; i += 4 * kStatsThreads) {
-      float4 v0 = p[i];
-      float4 v1 = (i + kStatsThreads < n4) ? p[i + kStatsThreads] : neg;
-      float4 v2 = (i + 2 * kStatsThreads < n4) ? p[i + 2 * kStatsThreads] : neg;
-      float4 v3 = (i + 3 * kStatsThreads < n4) ? p[i + 3 * kStatsThreads] : neg;
+      float4 v0 = stream_load4(p + i);
+      float4 v1 = (i + kStatsThreads < n4) ? stream_load4(p + i + kStatsThreads) : neg;
+      float4 v2 = (i + 2 * kStatsThreads < n4) ? stream_load4(p + i + 2 * kStatsThreads) : neg;
+      float4 v3 = (i + 3 * kStatsThreads < n4) ? stream_load4(p + i + 3 * kStatsThreads) : neg;
       float bm = fmaxf(fmaxf(max4(v0), max4(v1)), fmaxf(max4(v2), max4(v3)));
       if (bm > m) {
         s *= __expf(m - bm);     // m = -inf gives exp(-inf) = 0 and s is 0 anyway
@@ -104,63 +112,6 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* _
   }
 }
 
-// ---------------------------------------------------------------------------------------
-// decide: one 64-lane workgroup per server.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void decide_kernel(const int* __restrict__ cu_rows, int vocab, int n_chunks,
-                                                     const float2* __restrict__ partial,
-                                                     const float* __restrict__ logits, const float* __restrict__ q_probs,
-                                                     const int* __restrict__ draft_tokens,
-                                                     const float* __restrict__ u_accept, int* __restrict__ accepted_len,
-                                                     float* __restrict__ accept_stat, float* __restrict__ ratio_out,
-                                                     Decision* __restrict__ decision) {
-  const int srv = blockIdx.x;
-  const int row0 = cu_rows[srv];
-  const int gamma = cu_rows[srv + 1] - row0 - 1;
-  const int d0 = row0 - srv;
-  const int lane = threadIdx.x;
-
-  int first_reject = gamma;    // smallest rejected draft index seen by this lane
-  float stat = 0.f;
-  for (int j = lane; j < gamma; j += 64) {
-    const int row = row0 + j;
-    float m = -INFINITY, s = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-      float2 ps = partial[(size_t)row * n_chunks + c];
-      merge_pair(m, s, ps.x, ps.y);
-    }
-    const int tok = draft_tokens[d0 + j];
-    const float p = expf(logits[(size_t)row * vocab + tok] - m) / s;
-    const float q = q_probs[(size_t)(d0 + j) * vocab + tok];
-    const float ratio = (q == 0.f) ? INFINITY : p / q;
-    if (ratio_out) ratio_out[d0 + j] = ratio;
-    stat += fminf(1.f, ratio);
-    if (u_accept[d0 + j] > ratio) first_reject = min(first_reject, j);
-  }
-  for (int off = 32; off > 0; off >>= 1) {
-    first_reject = min(first_reject, __shfl_down(first_reject, off));
-    stat += __shfl_down(stat, off);
-  }
-  first_reject = __shfl(first_reject, 0);
-  if (lane == 0) {
-    const int m_acc = first_reject;
-    accepted_len[srv] = m_acc;
-    accept_stat[srv] = gamma > 0 ? stat / (float)gamma : 0.f;
-    const int row = row0 + m_acc;
-    float m = -INFINITY, s = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-      float2 ps = partial[(size_t)row * n_chunks + c];
-      merge_pair(m, s, ps.x, ps.y);
-    }
-    Decision d;
-    d.row = row;
-    d.q_row = (m_acc < gamma) ? d0 + m_acc : -1;
-    d.row_max = m;
-    d.inv_z = 1.f / s;
-    decision[srv] = d;
-  }
-}
-
 // Weight of token t in the draw: max(0, p - q) or p.
 __device__ __forceinline__ float draw_weight(float logit, float q, float row_max, float inv_z, bool residual) {
   float p = expf(logit - row_max) * inv_z;
@@ -200,34 +151,6 @@ __device__ __forceinline__ float sum8(const float w[8]) {
   return ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
 }
 
-// ---------------------------------------------------------------------------------------
-// residual_tiles: grid (tiles, servers).  force_p: redo a server's tiles with weights p
-// (only used when its residual had no mass).
-// ---------------------------------------------------------------------------------------
-template <bool VEC>
-__global__ __launch_bounds__(kTileThreads) void residual_tiles_kernel(const Decision* __restrict__ decision, int vocab,
-                                                                       const float* __restrict__ logits,
-                                                                       const float* __restrict__ q_probs,
-                                                                       double* __restrict__ tile_sums) {
-  const int tile = blockIdx.x, srv = blockIdx.y, n_tiles = gridDim.x;
-  const Decision d = decision[srv];
-  const bool residual = d.q_row >= 0;
-  const float* lrow = logits + (size_t)d.row * vocab;
-  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
-  float w[8];
-  load_weights8<VEC>(lrow, qrow, tile * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, residual, w);
-  double acc = (double)sum8(w);
-  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
-  __shared__ double part[kTileThreads / 64];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = part[0];
-    for (int wv = 1; wv < kTileThreads / 64; ++wv) t += part[wv];
-    tile_sums[(size_t)srv * n_tiles + tile] = t;
-  }
-}
-
 // Workgroup-wide scan of one double per lane (256 lanes).  Returns the inclusive sum and sets
 // excl to the inclusive sum of the previous lane (0 for lane 0), bit-identical to what that
 // lane returns, so "first lane whose inclusive sum crosses a threshold" is unique.
@@ -251,6 +174,127 @@ __device__ __forceinline__ double block_scan(double v, double* wave_tot /*[4] sh
   return v + add;
 }
 
+// Softmax statistics of one row from its chunk pairs.
+__device__ __forceinline__ void row_max_sum(const float2* __restrict__ partial, int row, int n_chunks, float& m,
+                                            float& s) {
+  m = -INFINITY;
+  s = 0.f;
+  const float2* p = partial + (size_t)row * n_chunks;
+#pragma unroll 8
+  for (int c = 0; c < n_chunks; ++c) {
+    const float2 ps = p[c];
+    merge_pair(m, s, ps.x, ps.y);
+  }
+}
+
+// The accept decisions of one server, computed by one wavefront (lanes over draft positions).
+// Returns the decision in every lane; lane 0 of a workgroup with write_out set stores the outputs.
+__device__ __forceinline__ Decision decide_server(int srv, const int* __restrict__ cu_rows, int vocab, int n_chunks,
+                                                  const float2* __restrict__ partial,
+                                                  const float* __restrict__ logits, const float* __restrict__ q_probs,
+                                                  const int* __restrict__ draft_tokens,
+                                                  const float* __restrict__ u_accept, bool write_out,
+                                                  int* __restrict__ accepted_len, float* __restrict__ accept_stat,
+                                                  float* __restrict__ ratio_out) {
+  const int lane = threadIdx.x & 63;
+  const int row0 = cu_rows[srv];
+  const int gamma = cu_rows[srv + 1] - row0 - 1;
+  const int d0 = row0 - srv;
+  int first_reject = gamma;    // smallest rejected draft index seen by this lane
+  float stat = 0.f;
+  for (int j = lane; j < gamma; j += 64) {
+    const int row = row0 + j;
+    const int tok = draft_tokens[d0 + j];
+    const float u = u_accept[d0 + j];
+    const float lg = logits[(size_t)row * vocab + tok];
+    const float q = q_probs[(size_t)(d0 + j) * vocab + tok];
+    float m, s;
+    row_max_sum(partial, row, n_chunks, m, s);
+    const float p = expf(lg - m) / s;
+    const float ratio = (q == 0.f) ? INFINITY : p / q;
+    if (write_out && ratio_out) ratio_out[d0 + j] = ratio;
+    stat += fminf(1.f, ratio);
+    if (u > ratio) first_reject = min(first_reject, j);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    first_reject = min(first_reject, __shfl_xor(first_reject, off));
+    stat += __shfl_xor(stat, off);
+  }
+  const int m_acc = first_reject;
+  if (write_out && lane == 0) {
+    accepted_len[srv] = m_acc;
+    accept_stat[srv] = gamma > 0 ? stat / (float)gamma : 0.f;
+  }
+  Decision d;
+  d.row = row0 + m_acc;
+  d.q_row = (m_acc < gamma) ? d0 + m_acc : -1;
+  float m, s;
+  row_max_sum(partial, d.row, n_chunks, m, s);
+  d.row_max = m;
+  d.inv_z = 1.f / s;
+  return d;
+}
+
+// ---------------------------------------------------------------------------------------
+// draw_tiles: grid (tile groups, servers), 256 lanes.  A workgroup owns kTilesPerGroup
+// consecutive 2048-token tiles; group 0 also stores the server's outputs and its decision.
+// ---------------------------------------------------------------------------------------
+constexpr int kTilesPerGroup = 4;
+
+template <bool VEC>
+__global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __restrict__ cu_rows, int vocab,
+                                                                  int n_chunks, int n_tiles,
+                                                                  const float2* __restrict__ partial,
+                                                                  const float* __restrict__ logits,
+                                                                  const float* __restrict__ q_probs,
+                                                                  const int* __restrict__ draft_tokens,
+                                                                  const float* __restrict__ u_accept,
+                                                                  int* __restrict__ accepted_len,
+                                                                  float* __restrict__ accept_stat,
+                                                                  float* __restrict__ ratio_out,
+                                                                  Decision* __restrict__ decision,
+                                                                  double* __restrict__ tile_sums) {
+  const int group = blockIdx.x, srv = blockIdx.y;
+  __shared__ Decision sh_d;
+  __shared__ double part[kTileThreads / 64];
+  if (threadIdx.x < 64) {
+    const Decision dd = decide_server(srv, cu_rows, vocab, n_chunks, partial, logits, q_probs, draft_tokens, u_accept,
+                                      group == 0, accepted_len, accept_stat, ratio_out);
+    if (threadIdx.x == 0) {
+      sh_d = dd;
+      if (group == 0) decision[srv] = dd;
+    }
+  }
+  __syncthreads();
+  const Decision d = sh_d;
+  const bool residual = d.q_row >= 0;
+  const float* lrow = logits + (size_t)d.row * vocab;
+  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
+  // all loads of the group's tiles are issued before the first is consumed
+  float w[kTilesPerGroup][8];
+#pragma unroll
+  for (int k = 0; k < kTilesPerGroup; ++k) {
+    const int tile = group * kTilesPerGroup + k;
+    if (tile < n_tiles)
+      load_weights8<VEC>(lrow, qrow, tile * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, residual, w[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < kTilesPerGroup; ++k) {
+    const int tile = group * kTilesPerGroup + k;
+    if (tile >= n_tiles) break;
+    double acc = (double)sum8(w[k]);
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = part[0];
+      for (int wv = 1; wv < kTileThreads / 64; ++wv) t += part[wv];
+      tile_sums[(size_t)srv * n_tiles + tile] = t;
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // pick_token: one workgroup per server.
 // ---------------------------------------------------------------------------------------
@@ -271,15 +315,18 @@ __global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision
   __shared__ int sh_tile, sh_found, sh_last_pos;
   float w[8];
 
-  // total mass (sequential over the few tile sums, one lane: deterministic)
-  if (threadIdx.x == 0) {
-    double tot = 0.0;
-    for (int t = 0; t < n_tiles; ++t) tot += tile_sums[(size_t)srv * n_tiles + t];
-    sh_prefix = tot;
+  // total mass: workgroup scan over the tile sums (fixed order: deterministic)
+  const double* sums = tile_sums + (size_t)srv * n_tiles;
+  double total = 0.0;
+  for (int base = 0; base < n_tiles; base += kTileThreads) {
+    const int t = base + threadIdx.x;
+    double ex;
+    const double incl = block_scan(t < n_tiles ? sums[t] : 0.0, wave_tot, ex);
+    if (threadIdx.x == kTileThreads - 1) sh_prefix = incl;
+    __syncthreads();
+    total += sh_prefix;
+    __syncthreads();
   }
-  __syncthreads();
-  double total = sh_prefix;
-  __syncthreads();
 
   const bool fallback = residual && !(total > 0.0);   // residual without mass: draw from p instead
   if (fallback) {
@@ -308,24 +355,47 @@ __global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision
   __syncthreads();
 
   if (!fallback) {
+    // the tile in which the running sum crosses the target: exactly one lane sees the crossing
+    __shared__ int sh_last_tile;
+    __shared__ double sh_carry;
     if (threadIdx.x == 0) {
-      double run = 0.0;
-      int t = 0;
-      for (; t < n_tiles; ++t) {
-        double nxt = run + tile_sums[(size_t)srv * n_tiles + t];
-        if (nxt > target) break;
-        run = nxt;
-      }
-      if (t == n_tiles) {          // rounding left no crossing: last tile with mass
-        t = n_tiles - 1;
-        while (t > 0 && !(tile_sums[(size_t)srv * n_tiles + t] > 0.0)) --t;
-        run = 0.0;
-        for (int k = 0; k < t; ++k) run += tile_sums[(size_t)srv * n_tiles + k];
-      }
-      sh_tile = t;
-      sh_prefix = run;
+      sh_tile = -1;
+      sh_last_tile = 0;
     }
     __syncthreads();
+    double carry = 0.0;
+    for (int base = 0; base < n_tiles; base += kTileThreads) {
+      const int t = base + threadIdx.x;
+      const double v = t < n_tiles ? sums[t] : 0.0;
+      double ex;
+      const double incl = block_scan(v, wave_tot, ex);
+      if ((carry + incl > target) && !(carry + ex > target)) {
+        sh_tile = t;
+        sh_prefix = carry + ex;
+      }
+      if (v > 0.0) atomicMax(&sh_last_tile, t);
+      if (threadIdx.x == kTileThreads - 1) sh_carry = carry + incl;
+      __syncthreads();
+      carry = sh_carry;
+      const bool done = sh_tile >= 0;
+      __syncthreads();
+      if (done) break;
+    }
+    if (sh_tile < 0) {             // rounding left no crossing: the last tile with mass
+      carry = 0.0;
+      for (int base = 0; base < n_tiles; base += kTileThreads) {
+        const int t = base + threadIdx.x;
+        double ex;
+        const double incl = block_scan(t < n_tiles ? sums[t] : 0.0, wave_tot, ex);
+        if (t == sh_last_tile) sh_prefix = carry + ex;
+        if (threadIdx.x == kTileThreads - 1) sh_carry = carry + incl;
+        __syncthreads();
+        carry = sh_carry;
+        __syncthreads();
+      }
+      if (threadIdx.x == 0) sh_tile = sh_last_tile;
+      __syncthreads();
+    }
   }
 
   // Walk tiles: a single tile in the normal path, all tiles until found in the fallback path.
@@ -403,7 +473,7 @@ AcceptPlan plan_accept(int n_servers, int n_rows, int vocab, void* workspace) {
 
 }  // namespace
 
-// Enqueues the four kernels; arguments already validated.  n_rows = sum(gamma + 1).
+// Enqueues the kernels; arguments already validated.  n_rows = sum(gamma + 1).
 gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
                         const float* q_probs, const int* draft_tokens, const float* u_accept,
                         const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream) {
@@ -416,19 +486,21 @@ gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab
   else
     row_stats_kernel<false><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.partial);
   GS_LAUNCH_CHECK("row_stats");
-  decide_kernel<<<n_servers, 64, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.partial, target_logits, q_probs,
-                                              draft_tokens, u_accept, out->accepted_len, out->accept_stat,
-                                              out->ratio, p.decision);
-  GS_LAUNCH_CHECK("decide");
-  dim3 g3(p.n_tiles, n_servers);
+  dim3 g2(ceil_div(p.n_tiles, kTilesPerGroup), n_servers);
   if (vec) {
-    residual_tiles_kernel<true><<<g3, kTileThreads, 0, stream>>>(p.decision, vocab, target_logits, q_probs, p.tile_sums);
-    GS_LAUNCH_CHECK("residual_tiles");
+    draw_tiles_kernel<true><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, p.partial,
+                                                             target_logits, q_probs, draft_tokens, u_accept,
+                                                             out->accepted_len, out->accept_stat, out->ratio,
+                                                             p.decision, p.tile_sums);
+    GS_LAUNCH_CHECK("draw_tiles");
     pick_token_kernel<true><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
                                                                     q_probs, p.tile_sums, u_resample, out->next_token);
   } else {
-    residual_tiles_kernel<false><<<g3, kTileThreads, 0, stream>>>(p.decision, vocab, target_logits, q_probs, p.tile_sums);
-    GS_LAUNCH_CHECK("residual_tiles");
+    draw_tiles_kernel<false><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, p.partial,
+                                                              target_logits, q_probs, draft_tokens, u_accept,
+                                                              out->accepted_len, out->accept_stat, out->ratio,
+                                                              p.decision, p.tile_sums);
+    GS_LAUNCH_CHECK("draw_tiles");
     pick_token_kernel<false><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
                                                                      q_probs, p.tile_sums, u_resample, out->next_token);
   }
