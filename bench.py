@@ -22,6 +22,22 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+# profiles/hbm_traffic_counters.md (121.84 MB fetched + 6.40 MB written, scaled by the copy-kernel factors
+# given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
+GEMM_TRAFFIC = {"gemm_hip_sha256": "076b3be3384b9b63a5e29631b6219d2fcaa57281e4d70a48b92fc325dd6c86a7",
+                "bytes_per_launch": 128234656}
+
+
+def measured_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_2512_09963_amd", "csrc", "gemm.hip")
+    try:
+        h = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    return GEMM_TRAFFIC["bytes_per_launch"] if h == GEMM_TRAFFIC["gemm_hip_sha256"] else None
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -31,6 +47,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (result is marked invalid)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-accept-leg", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (reference dispatches for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -195,13 +213,21 @@ def main():
     torch.cuda.synchronize()
     stages = ver.gs_profile_read()
     ver.gs_profile_enable(False)
+    # what an event pair measures with nothing between its two records (the bracket's own cost)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    for a, b in pairs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    pair_us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)[len(pairs) // 2]
 
     ms_step = dt * 1e3 / args.steps
     emitted = float(w["host"]["accepted_len"].sum().item() + db.n_servers)
     gemm_ms, gemm_launches = stages["gemm"]
     w_bytes = projection_weight_bytes(ms)
-    gemm_ms_step = gemm_ms / args.steps
-    achieved = w_bytes / (gemm_ms_step * 1e-3) / 1e9
+    gemm_us_raw = gemm_ms * 1e3 / gemm_launches
+    gemm_us = gemm_us_raw - pair_us                  # kernel alone: bracket minus the empty-bracket cost
+    achieved = w_bytes / (gemm_launches / args.steps) / (gemm_us * 1e-6) / 1e9
     res = {
         "metric": "verified_tokens_per_s", "value": round(db.n_draft / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
@@ -213,13 +239,20 @@ def main():
         "emitted_tokens_per_s": round(emitted / (ms_step * 1e-3), 1),
         "roofline": {"kernel": "gemm_bf16_skinny (all projections of a step)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
                      "bytes_per_launch": round(w_bytes / (gemm_launches / args.steps)),
-                     "us_per_launch": round(gemm_ms * 1e3 / gemm_launches, 2)},
+                     "us_per_launch": round(gemm_us, 2), "us_per_launch_event_bracket": round(gemm_us_raw, 2),
+                     "event_pair_overhead_us": round(pair_us, 2)},
         "stage_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in stages.items()},
     }
     if args.layers:
         res["invalid"] = "debug run with fewer layers"
+    if args.calibrate_copy:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.skip_accept_leg:
         res["accept_kernel"] = accept_leg(seed)
     if not args.skip_cpu_baseline:
