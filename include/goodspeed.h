@@ -131,15 +131,27 @@ typedef struct {
   int dtype;            /* GS_F32 or GS_BF16: storage type of weights, KV pages and GEMM operands */
 } gs_model_desc;
 
-/* All matrices are row-major [out_features, in_features] in the model dtype. */
+/*
+ * Projection matrices are logically [out_features, in_features] in the model dtype and must be
+ * given in the layout gs_pack_weight produces (one-time repack at load):
+ *   GS_F32 : row-major, unchanged
+ *   GS_BF16: tile-packed [out/16][in/64][2][64][8]: for a tile of 16 output rows and a step of 64
+ *            inputs, lane l = 16 g + c (c = row in tile, g = 0..3) owns inputs 16 g .. 16 g + 15 of
+ *            row c, the first 8 in half 0 and the last 8 in half 1; so the 2 KB one wavefront needs
+ *            per step are contiguous, and so are the steps of a tile.
+ * The embedding table is gathered by row and stays row-major.
+ */
+gs_status gs_pack_weight(const void* w_rowmajor /* dev */, void* w_packed /* dev, same size, not in place */,
+                         int n_out, int k_in, int dtype, void* hip_stream);
+
 typedef struct {
-  const void* embed;          /* dev [V, d]                                              */
-  const void* lm_head;        /* dev [V, d]                                              */
+  const void* embed;          /* dev [V, d] row-major                                    */
+  const void* lm_head;        /* dev [V, d] packed                                       */
   const float* final_norm;    /* dev [d] fp32                                            */
-  const void* const* wqkv;    /* host [n_layers] of dev [(H + 2 H_kv) hd, d]: Q heads, K heads, V heads */
-  const void* const* wo;      /* host [n_layers] of dev [d, H hd]                        */
-  const void* const* wgu;     /* host [n_layers] of dev [2 F, d]: gate rows, then up rows */
-  const void* const* wd;      /* host [n_layers] of dev [d, F]                           */
+  const void* const* wqkv;    /* host [n_layers] of dev packed [(H + 2 H_kv) hd, d]: Q, K, V heads */
+  const void* const* wo;      /* host [n_layers] of dev packed [d, H hd]                 */
+  const void* const* wgu;     /* host [n_layers] of dev packed [2 F, d]: gate rows, up rows */
+  const void* const* wd;      /* host [n_layers] of dev packed [d, F]                    */
   const float* const* norm1;  /* host [n_layers] of dev [d] fp32 (attention pre-norm)    */
   const float* const* norm2;  /* host [n_layers] of dev [d] fp32 (FFN pre-norm)          */
 } gs_weights;

@@ -21,7 +21,7 @@ GS_F32, GS_BF16 = 0, 1
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_schedule_gamma",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -90,6 +90,8 @@ def lib():
                                           C.POINTER(gs_accept_out), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
             L.gs_profile_enable.restype = C.c_int
             L.gs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+            L.gs_pack_weight.restype = C.c_int
+            L.gs_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
             L.gs_trace_residual.restype = C.c_int
             L.gs_trace_residual.argtypes = [C.c_void_p, C.c_void_p]
             L.gs_profile_read.restype = C.c_int
@@ -160,6 +162,14 @@ def gs_schedule_gamma(accepted_len, accept_stat, gamma_prev, alpha_hat, x_smooth
                                    x_smooth.ctypes.data, float(eta), float(beta), int(capacity), int(gamma_min),
                                    int(gamma_max), nxt.ctypes.data))
     return nxt
+
+
+def gs_pack_weight(w, stream=None):
+    """Returns a new device tensor holding the [out, in] matrix `w` in the library's projection layout."""
+    out = torch.empty_like(w)
+    dtype = GS_BF16 if w.dtype == torch.bfloat16 else GS_F32
+    _check(lib().gs_pack_weight(_ptr(w), _ptr(out), int(w.shape[0]), int(w.shape[1]), dtype, _stream(stream)))
+    return out
 
 
 class Verifier:

@@ -11,6 +11,7 @@
 namespace gs {
 
 int gemm_splits(int dtype, int M, int N, int K);
+gs_status launch_pack_weight(const void* src, void* dst, int N, int K, hipStream_t stream);
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream);
 gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
@@ -124,6 +125,22 @@ __global__ void gather_draft_tokens_kernel(const int* __restrict__ tokens, const
 }
 
 }  // namespace
+
+extern "C" gs_status gs_pack_weight(const void* w_rowmajor, void* w_packed, int n_out, int k_in, int dtype,
+                                    void* hip_stream) {
+  if (!w_rowmajor || !w_packed) return gs::fail(GS_EINVAL, "null argument");
+  if (w_rowmajor == w_packed) return gs::fail(GS_EINVAL, "gs_pack_weight does not work in place");
+  if (n_out <= 0 || k_in <= 0) return gs::fail(GS_EINVAL, "matrix dimensions must be positive");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (dtype == GS_F32) {
+    GS_HIP_CHECK(hipMemcpyAsync(w_packed, w_rowmajor, sizeof(float) * (size_t)n_out * k_in, hipMemcpyDeviceToDevice,
+                                stream));
+    return GS_OK;
+  }
+  if (dtype != GS_BF16) return gs::fail(GS_EINVAL, "dtype must be GS_F32 or GS_BF16");
+  if (n_out % 64 || k_in % 64) return gs::fail(GS_ESHAPE, "bf16 matrices need both dimensions to be multiples of 64");
+  return gs::launch_pack_weight(w_rowmajor, w_packed, n_out, k_in, stream);
+}
 
 extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, gs_ctx** out) {
   if (!desc || !w || !out) return gs::fail(GS_EINVAL, "null argument");

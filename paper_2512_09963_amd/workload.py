@@ -27,12 +27,13 @@ def to_device(a, dtype):
 def upload_model(ms: synth.ModelShape, top: dict, get_layer):
     """Returns a binding.Verifier for weights given as float32 numpy arrays."""
     dt = storage_dtype(ms)
-    top_d = {"embed": to_device(top["embed"], dt), "lm_head": to_device(top["lm_head"], dt),
+    packed = lambda a: gsb.gs_pack_weight(to_device(a, dt))      # the row-major upload is dropped after the repack
+    top_d = {"embed": to_device(top["embed"], dt), "lm_head": packed(top["lm_head"]),
              "final_norm": to_device(top["final_norm"], torch.float32)}
     layers = []
     for l in range(ms.n_layers):
         W = get_layer(l)
-        layers.append({k: to_device(W[k], dt) for k in ("wqkv", "wo", "wgu", "wd")} |
+        layers.append({k: packed(W[k]) for k in ("wqkv", "wo", "wgu", "wd")} |
                       {k: to_device(W[k], torch.float32) for k in ("norm1", "norm2")})
     desc = dict(n_layers=ms.n_layers, d_model=ms.d_model, n_heads=ms.n_heads, n_kv_heads=ms.n_kv_heads,
                 head_dim=ms.head_dim, d_ffn=ms.d_ffn, vocab=ms.vocab, rope_theta=ms.rope_theta, rms_eps=ms.rms_eps,
