@@ -23,10 +23,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-# profiles/hbm_traffic_counters.md (121.84 MB fetched + 6.40 MB written, scaled by the copy-kernel factors
+# profiles/hbm_traffic_counters.md (121.78 MB fetched + 6.40 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "076b3be3384b9b63a5e29631b6219d2fcaa57281e4d70a48b92fc325dd6c86a7",
-                "bytes_per_launch": 128234656}
+GEMM_TRAFFIC = {"gemm_hip_sha256": "bde3b0821217f2f3fb8f07a9e1c1f6fe1e1c1ef157a83d4e896c0388d0df94b1",
+                "bytes_per_launch": 128181401}
 
 
 def measured_traffic():
@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (result is marked invalid)")
+    ap.add_argument("--workload", choices=["cfg3", "cfg4", "cfg5"], default="cfg3",
+                    help="cfg3 (default) is the configuration the metric is quoted on; cfg4 (32 ragged servers, "
+                         "paged) and cfg5 (70B shape) are extra measurements")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-accept-leg", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -52,12 +55,22 @@ def parse():
     return ap.parse_args()
 
 
-def build_workload(ms, seed):
+WORKLOADS = {
+    "cfg3": "llama3-8b-shaped verify (32 layers, d 4096, 32q/8kv heads, ffn 14336, vocab 128256), "
+            "8 draft servers, gamma U[3,8], ctx 2048, 16-token KV pages",
+    "cfg4": "llama3-8b-shaped verify, 32 draft servers, gamma U[1,16], ctx log-uniform [512,8192], "
+            "permuted 16-token KV pages",
+    "cfg5": "llama3-70b-shaped verify (80 layers, d 8192, 64q/8kv heads, ffn 28672, vocab 128256), "
+            "16 draft servers, gamma U[2,8], ctx 4096",
+}
+
+
+def build_workload(ms, seed, name="cfg3"):
     import torch
     from paper_2512_09963_amd import synth, workload as wl
-    cfg = synth.config3(seed, ms)
+    cfg = {"cfg3": synth.config3, "cfg4": synth.config4, "cfg5": synth.config5}[name](seed, ms)
     t0 = time.time()
-    ver, kv, db = wl.upload_config(cfg)
+    ver, kv, db = wl.upload_config(cfg, progress=True)
     torch.cuda.synchronize()
     print(f"[bench] weights + KV generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
     return dict(ver=ver, kv=kv, db=db, batch=cfg.batch, tokens=cfg.tokens, q=cfg.q_probs, ua=cfg.u_accept,
@@ -186,10 +199,10 @@ def main():
         sys.exit(1)
     gsb.lib()
     seed = synth.MASTER_SEED
-    ms = synth.LLAMA3_8B
+    ms = synth.LLAMA3_70B if args.workload == "cfg5" else synth.LLAMA3_8B
     if args.layers:
         ms = dataclasses.replace(ms, n_layers=args.layers)
-    w = build_workload(ms, seed)
+    w = build_workload(ms, seed, args.workload)
     db, ver = w["db"], w["ver"]
     dev = torch.device("cuda:0")
     w["ws"] = torch.empty(ver.gs_workspace_bytes(db.n_rows, db.n_servers, db.max_ctx), dtype=torch.uint8, device=dev)
@@ -232,8 +245,7 @@ def main():
         "metric": "verified_tokens_per_s", "value": round(db.n_draft / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama3-8b-shaped verify (32 layers, d 4096, 32q/8kv heads, ffn 14336, vocab 128256), "
-                               "8 draft servers, gamma U[3,8], ctx 2048, 16-token KV pages",
+        "config": {"workload": WORKLOADS[args.workload],
                    "n_servers": db.n_servers, "draft_tokens": db.n_draft, "target_rows": db.n_rows,
                    "gamma": [int(g) for g in db.gamma]},
         "emitted_tokens_per_s": round(emitted / (ms_step * 1e-3), 1),
@@ -253,9 +265,9 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.skip_accept_leg:
+    if not args.skip_accept_leg and args.workload == "cfg3":
         res["accept_kernel"] = accept_leg(seed)
-    if not args.skip_cpu_baseline:
+    if not args.skip_cpu_baseline and args.workload == "cfg3":
         res["cpu_baseline"] = cpu_baseline(ms, w, seed)
     print(json.dumps(res), flush=True)
 

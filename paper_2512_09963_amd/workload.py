@@ -24,7 +24,12 @@ def to_device(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a)).to(_dev()).to(dtype)
 
 
-def upload_model(ms: synth.ModelShape, top: dict, get_layer):
+def _progress(msg):
+    import sys
+    print(msg, file=sys.stderr, flush=True)
+
+
+def upload_model(ms: synth.ModelShape, top: dict, get_layer, progress=False):
     """Returns a binding.Verifier for weights given as float32 numpy arrays."""
     dt = storage_dtype(ms)
     packed = lambda a: gsb.gs_pack_weight(to_device(a, dt))      # the row-major upload is dropped after the repack
@@ -35,6 +40,8 @@ def upload_model(ms: synth.ModelShape, top: dict, get_layer):
         W = get_layer(l)
         layers.append({k: packed(W[k]) for k in ("wqkv", "wo", "wgu", "wd")} |
                       {k: to_device(W[k], torch.float32) for k in ("norm1", "norm2")})
+        if progress and (l + 1) % 8 == 0:
+            _progress(f"[workload] uploaded {l + 1}/{ms.n_layers} layers")
     desc = dict(n_layers=ms.n_layers, d_model=ms.d_model, n_heads=ms.n_heads, n_kv_heads=ms.n_kv_heads,
                 head_dim=ms.head_dim, d_ffn=ms.d_ffn, vocab=ms.vocab, rope_theta=ms.rope_theta, rms_eps=ms.rms_eps,
                 dtype=ms.dtype)
@@ -96,16 +103,18 @@ def verify(ver: gsb.Verifier, kv: KVCache, db: DeviceBatch, workspace=None, want
     return out, logits, workspace
 
 
-def upload_config(cfg: synth.VerifyConfig, ver=None):
+def upload_config(cfg: synth.VerifyConfig, ver=None, progress=False):
     """Device side of a synth.VerifyConfig: model (random init from the seed), synthetic KV, batch."""
     ms, seed, batch = cfg.ms, cfg.seed, cfg.batch
     if ver is None:
         top = synth.top_weights(ms, seed)
-        ver = upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l))
+        ver = upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l), progress)
         del top
     kv = KVCache(ms, batch.n_pages, batch.page_size, zero=False)
     for l in range(ms.n_layers):
         kv.set_layer(l, synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, batch.page_size),
                      synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, batch.page_size))
+        if progress and (l + 1) % 16 == 0:
+            _progress(f"[workload] KV of {l + 1}/{ms.n_layers} layers in place")
     db = DeviceBatch(batch, cfg.tokens, cfg.q_probs, cfg.u_accept, cfg.u_resample)
     return ver, kv, db

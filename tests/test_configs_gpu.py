@@ -98,6 +98,8 @@ def _verify_and_compare(cfg, ver, kv, db, state=None):
         x_free = fw.layer_forward(ms, x_free, W, k_fr, v_fr, *args)
         _record_rows(l, b, k_fr, v_fr, state.free)
         del W, k_tf, v_tf, k_fr, v_fr
+        if (l + 1) % 8 == 0:
+            print(f"[oracle] {cfg.name}: layer {l + 1}/{ms.n_layers} checked", flush=True)
     assert worst_layer <= 2e-2, f"teacher-forced layer output error / row scale = {worst_layer:.3g}"
     assert worst_kv <= 2e-2, f"appended K/V rows: {worst_kv:.3g}"
     head_err = assert_logits_close(got_logits, fw.lm_head(ms, tr[ms.n_layers], top), 2e-2, "teacher-forced logits")
@@ -119,7 +121,7 @@ def _verify_and_compare(cfg, ver, kv, db, state=None):
 def test_config3_llama8b_shape_full_size():
     from paper_2512_09963_amd import workload as wl
     cfg = synth.config3()
-    ver, kv, db = wl.upload_config(cfg)
+    ver, kv, db = wl.upload_config(cfg, progress=True)
     _verify_and_compare(cfg, ver, kv, db)
 
 
@@ -129,7 +131,7 @@ def test_config4_ragged_paged_with_scheduler_in_the_loop():
     from paper_2512_09963_amd import binding as gsb, workload as wl
     ms = synth.LLAMA3_8B if FULL else dataclasses.replace(synth.LLAMA3_8B, n_layers=4)
     cfg = synth.config4(ms=ms)
-    ver, kv, db = wl.upload_config(cfg)
+    ver, kv, db = wl.upload_config(cfg, progress=True)
     n, C = cfg.batch.n_servers, 272
     alpha, X = np.full(n, 0.5), np.ones(n)
     alpha_o, X_o = alpha.copy(), X.copy()
@@ -161,5 +163,5 @@ def test_config5_llama70b_shape():
     from paper_2512_09963_amd import workload as wl
     ms = synth.LLAMA3_70B if FULL else dataclasses.replace(synth.LLAMA3_70B, n_layers=4)
     cfg = synth.config5(ms=ms)
-    ver, kv, db = wl.upload_config(cfg)
+    ver, kv, db = wl.upload_config(cfg, progress=True)
     _verify_and_compare(cfg, ver, kv, db)
