@@ -15,7 +15,7 @@ import numpy as np
 import torch  # imported before the library so that both share one HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgoodspeed.so")
+LIB_PATH = os.environ.get("GS_LIB_PATH") or os.path.join(_HERE, "libgoodspeed.so")   # override: development builds
 
 GS_F32, GS_BF16 = 0, 1
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}

@@ -5,17 +5,18 @@
 //   K pages [page][H_kv][slot][hd]   (key-major: a key's head vector is contiguous)
 //   V pages [page][H_kv][hd][slot]   (transposed: the slots of one channel are contiguous)
 //
-// bf16 path (MFMA, no LDS staging of K/V): one workgroup per (server, KV head, KV split), one
-// wave per 16 of the T_i * G query rows that share the KV head (token-major, head-minor), so
-// each K/V byte leaves HBM once per workgroup and the other waves hit it in cache.
-//   S^T = K Q^T : A operand = 16 keys x 32 channels read straight from the K page (16 bytes
-//                 per lane), B operand = Q rows (kept in registers for the whole kernel).
+// bf16 path (MFMA): one workgroup per (server, KV head, KV split), one wave per 16 of the
+// T_i * G query rows that share the KV head (token-major, head-minor), so each K/V byte leaves
+// HBM once per workgroup; K/V stream through an LDS ring filled by direct global->LDS loads.
+//   S^T = K Q^T : A operand = 16 keys x 32 channels, B operand = Q rows (kept in registers).
 //   The result layout puts a query row in lane%16 and 4 consecutive keys in each lane, which
 //   is already the A-operand layout of the second product, so P never leaves registers:
-//   O = P V     : B operand = V^T read straight from the transposed V page (8 bytes = 4
-//                 keys of one channel per lane).
-// The online-softmax state (running max, running sum) lives per query row in lane%16.
-// Partial results of the splits are merged by combine_kernel.
+//   O = P V     : B operand = V^T, 4 keys of one channel per lane, read from the verbatim copy
+//                 of the transposed V page.
+// The online-softmax state (running max, running sum) lives per query row in lane%16.  The
+// number of KV splits of a server follows its own context length (a fixed number of 32-key steps
+// per workgroup), so ragged batches stay balanced.  Partial results of the splits are merged by
+// attn_combine_kernel.
 //
 // fp32 path: one wave per (row, head), lanes over keys, online softmax per lane.
 #include "common.h"
@@ -93,41 +94,93 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
   }
 }
 
+#ifndef GS_ATTN_WGS
+#define GS_ATTN_WGS 768
+#endif
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA path.  grid (n_splits, H_kv, N); one wave per 16-row query tile (blockDim = 64 *
-// tiles); the waves of a workgroup read the same K/V (served by L1/L2 after the first) and
-// never synchronise.  partial_o [R][H][n_splits][HD] fp32, partial_ml [R][H][n_splits][2].
+// bf16 MFMA path.  grid (max_splits, H_kv, N), NW waves per workgroup.
+//
+// A workgroup owns steps [split * steps_per_split, ...) of one (server, KV head); a step is 32
+// keys = two 16-key tiles = 16 KB of K and V at hd 128.  K/V go from global memory straight into
+// a two-stage LDS buffer with direct global->LDS loads (no register staging).  A stage has four
+// parts, K and V of either tile; part p is loaded by wave p % NW (waves 0..3 when NW > 4), whose
+// HD/32 load instructions of 1 KB each share one scalar base address.  One barrier per step both
+// publishes the stage that has landed and frees the stage that is refilled next.  K is placed in
+// LDS in MFMA-fragment order (lane l of fragment (tile, ks) finds its 16 bytes at fragment * 1 KB
+// + l * 16); V pages are copied verbatim ([channel][16 slots] per tile), which the second product
+// reads as 8-byte pieces without bank conflicts.
+// Wave w computes query tile w (16 of the T_i * G rows that share the KV head, token-major,
+// head-minor): S^T = K Q^T, online softmax per query row (lane%16), O += P V with P as a two-term
+// bf16 sum.  partial_o [R][H][max_splits][HD] fp32, partial_ml [R][H][max_splits][2]; splits
+// beyond a server's own count are never written and never read.
 // ------------------------------------------------------------------------------------------
-template <int HD, int G>
-__global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict__ q,
-                                                         const bf16_t* __restrict__ k_pages,
-                                                         const bf16_t* __restrict__ v_pages,
-                                                         const int* __restrict__ block_table, int max_blocks,
-                                                         const int* __restrict__ cu_rows,
-                                                         const int* __restrict__ ctx_len, int page_size, int n_heads,
-                                                         int n_kv, int n_splits, int q_row_offset,
-                                                         float* __restrict__ partial_o,
-                                                         float* __restrict__ partial_ml) {
-  constexpr int KS = HD / 32;   // k steps of the first product
-  constexpr int DT = HD / 16;   // channel tiles of the second product
+__device__ __forceinline__ void wait_all_vector_loads() {
+  // s_waitcnt vmcnt(0) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8;
+  // the other two fields at their maximum mean "do not wait")
+  __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));
+}
+
+// Reductions over the four 16-lane rows of a wave (lanes c, c+16, c+32, c+48), result in every lane.
+// The two swap instructions exchange rows between a register pair; fed the same value twice they
+// return (rows 0,0,2,2 | rows 1,1,3,3) and then (low half twice | high half twice).
+__device__ __forceinline__ float rows_max(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <int HD, int G, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __restrict__ q,
+                                                            const bf16_t* __restrict__ k_pages,
+                                                            const bf16_t* __restrict__ v_pages,
+                                                            const int* __restrict__ block_table, int max_blocks,
+                                                            const int* __restrict__ cu_rows,
+                                                            const int* __restrict__ ctx_len, int page_size,
+                                                            int n_heads, int n_kv, int steps_per_split,
+                                                            int max_splits, int q_row_offset,
+                                                            float* __restrict__ partial_o,
+                                                            float* __restrict__ partial_ml) {
+  constexpr int KS = HD / 32;            // k steps of the first product = 1 KB loads per part
+  constexpr int DT = HD / 16;            // channel tiles of the second product
+  constexpr int PART = HD * 32;          // bytes of K (or V) of one 16-key tile
+  constexpr int STAGE = 4 * PART;        // K tile 0, K tile 1, V tile 0, V tile 1
+  __shared__ __attribute__((aligned(16))) unsigned char ring[2 * STAGE];
+
   const int split = blockIdx.x, kh = blockIdx.y, srv = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // provably uniform: scalar page lookups
   const int g = lane >> 4, c = lane & 15;
   const int row0 = cu_rows[srv];
   const int T = cu_rows[srv + 1] - row0;
   const int L = ctx_len[srv];
   const int n_keys = L + T;
-  const int tile_row0 = q_row_offset + wave * 16;   // first query row (token-major, head-minor) of this wave
-  const int rows = T * G - tile_row0;                // valid rows in this tile (may exceed 16)
-  if (rows <= 0) return;
+  const int n_steps_all = (n_keys + 31) >> 5;
+  const int step_begin = split * steps_per_split;
+  if (step_begin >= n_steps_all) return;                                // this server has fewer splits
+  const int n = min(steps_per_split, n_steps_all - step_begin);        // steps of this workgroup
   const int* bt = block_table + (size_t)srv * max_blocks;
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);   // scores in log2 units
+  const bool page_pow2 = (page_size & (page_size - 1)) == 0;
+  const int page_shift = 31 - __builtin_clz(page_size);
+  const int last_tile_key = ((n_keys - 1) >> 4) << 4;                   // first key of the last existing tile
 
-  // Q fragment (B operand of the first product): query row = c, channels ks*32 + g*8 ..
+  // ---- this wave's query tile
+  const int tile_row0 = q_row_offset + wave * 16;
+  const int rows = T * G - tile_row0;                                   // valid rows of the tile (<= 0: none)
+  const bool has_rows = rows > 0;
   const int my_lr = tile_row0 + c;
   const bool my_ok = c < rows;
   const int my_j = my_ok ? my_lr / G : 0, my_hg = my_ok ? my_lr - my_j * G : 0;
-  const int limit = my_ok ? L + my_j : -1;           // last key this lane's query row may see
+  const int limit = my_ok ? L + my_j : -1;                              // last key this lane's row may see
+  const int j_max = min(T - 1, (tile_row0 + 15) / G);
+  const int my_step_end = has_rows ? ((L + j_max) >> 5) + 1 : 0;       // causal: no key beyond L + j_max
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   bf16x8_t qf[KS];
   {
     const bf16_t* src = q + ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * HD + g * 8;
@@ -143,138 +196,179 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int n_steps = (n_keys + 31) >> 5;
-  const int per_split = (n_steps + n_splits - 1) / n_splits;
-  const int step_begin = split * per_split;
-  // a tile whose rows all belong to block tokens < j_max sees no key beyond L + j_max
-  const int j_max = min(T - 1, (tile_row0 + 15) / G);
-  const int step_end = min(min(n_steps, step_begin + per_split), ((L + j_max) >> 5) + 1);
-  const int last_tile_key = ((n_keys - 1) >> 4) << 4;   // first key of the last 16-key tile that exists
-
-  auto tile_base = [&](int step, int t, int& page, int& slot0) {
-    const int key0 = min(step * 32 + t * 16, last_tile_key);   // a tile past the end re-reads the last one (masked)
-    page = bt[key0 / page_size];
-    slot0 = key0 % page_size;
-  };
-  auto load_k = [&](int page, int slot0, uint4 (&kraw)[KS]) {
-    const bf16_t* kp = k_pages + (((size_t)page * n_kv + kh) * page_size + slot0 + c) * HD + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kraw[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
-  };
-  int page_cur[2] = {0, 0}, slot_cur[2] = {0, 0};
-  uint4 k_cur[2][KS];
-  if (step_begin < step_end) {
+  // ---- page-table lookup of the two 16-key tiles of a step (scalar loads; done one iteration before
+  // the stage is issued, so that no load instruction waits for it)
+  auto lookup = [&](int step, int (&page)[2], int (&slot0)[2]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      tile_base(step_begin, t, page_cur[t], slot_cur[t]);
-      load_k(page_cur[t], slot_cur[t], k_cur[t]);
+      const int key0 = min(step * 32 + t * 16, last_tile_key);   // a tile past the end re-reads the last one
+      // (page sizes are powers of two in practice: shifts instead of a scalar division sequence)
+      const int blk = page_pow2 ? key0 >> page_shift : key0 / page_size;
+      page[t] = bt[blk];
+      slot0[t] = key0 - blk * page_size;
     }
-  }
+  };
+  // ---- stage loader.  Part p (0, 1: K of tile 0, 1; 2, 3: V of tile 0, 1) belongs to one wave; its
+  // address is a wave-uniform base (scalar registers) plus a per-lane byte offset that never changes:
+  //   K: lane (c, g) of fragment ks holds key slot0 + c, channels ks*32 + g*8 ..
+  //   V: 16-byte piece ch*64 + lane of the [HD][16 slots] tile is channel ch*32 + lane/2, half lane%2
+  const unsigned k_lane_off = (unsigned)(c * HD + g * 8) * 2u;
+  const unsigned v_lane_off = (unsigned)((lane >> 1) * page_size + (lane & 1) * 8) * 2u;
+  const char* k_bytes = reinterpret_cast<const char*>(k_pages);
+  const char* v_bytes = reinterpret_cast<const char*>(v_pages);
+  auto issue = [&](int slot, const int (&page)[2], const int (&slot0)[2]) {
+    unsigned char* stage = ring + slot * STAGE;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      if (wave != (NW > 4 ? p : p % NW)) continue;           // uniform branch
+      const int t = p & 1;
+      const size_t head = (size_t)page[t] * n_kv + kh;
+      if (p < 2) {
+        const char* src = k_bytes + (head * page_size + slot0[t]) * (HD * 2) + k_lane_off;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          __builtin_amdgcn_global_load_lds(src + ks * 64,
+                                           (__attribute__((address_space(3))) void*)(stage + p * PART + ks * 1024),
+                                           16, 0, 0);
+      } else {
+        const char* src = v_bytes + (head * HD * page_size + slot0[t]) * 2 + v_lane_off;
+        const size_t stride = (size_t)64 * page_size;        // 32 channels
+#pragma unroll
+        for (int ch = 0; ch < KS; ++ch)
+          __builtin_amdgcn_global_load_lds(src + ch * stride,
+                                           (__attribute__((address_space(3))) void*)(stage + p * PART + ch * 1024),
+                                           16, 0, 0);
+      }
+    }
+  };
 
-  for (int step = step_begin; step < step_end; ++step) {
-    uint2 vraw[2][DT];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const bf16_t* vp = v_pages + (((size_t)page_cur[t] * n_kv + kh) * HD + c) * page_size + slot_cur[t] + g * 4;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vraw[t][dt] = *reinterpret_cast<const uint2*>(vp + (size_t)dt * 16 * page_size);
+  int pg_next[2], sl_next[2];
+  lookup(step_begin, pg_next, sl_next);
+  issue(0, pg_next, sl_next);
+  if (1 < n) lookup(step_begin + 1, pg_next, sl_next);
+
+  for (int s = 0; s < n; ++s) {
+    const int step = step_begin + s;
+    wait_all_vector_loads();     // this wave's parts of stage s have landed
+    __syncthreads();             // stage s complete for all waves; the other stage is free
+    if (s + 1 < n) {
+      issue((s + 1) & 1, pg_next, sl_next);
+      if (s + 2 < n) lookup(step + 2, pg_next, sl_next);     // for the next iteration's issue
     }
-    // first product S^T = K Q^T for the two 16-key tiles, then fetch the next step's K
+    if (step >= my_step_end) continue;
+
+    const unsigned char* base = ring + (s & 1) * STAGE;
+    // first product S^T = K Q^T for the two 16-key tiles
+    bf16x8_t kf[2 * KS];
+#pragma unroll
+    for (int i = 0; i < 2 * KS; ++i) kf[i] = *reinterpret_cast<const bf16x8_t*>(base + i * 1024 + lane * 16);
     floatx4_t sacc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       floatx4_t acc = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&k_cur[t][ks]), qf[ks], acc, 0,
-                                                      0, 0);
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t * KS + ks], qf[ks], acc, 0, 0, 0);
       sacc[t] = acc;
     }
-    if (step + 1 < step_end) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        tile_base(step + 1, t, page_cur[t], slot_cur[t]);
-        load_k(page_cur[t], slot_cur[t], k_cur[t]);
-      }
-    }
-    // keys past the end of the sequence inside the last page hold stale data: zero their V
-    if (step * 32 + 32 > n_keys) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int kbase = step * 32 + t * 16 + g * 4;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uint2 v = vraw[t][dt];
-          if (kbase + 0 >= n_keys) v.x &= 0xffff0000u;
-          if (kbase + 1 >= n_keys) v.x &= 0x0000ffffu;
-          if (kbase + 2 >= n_keys) v.y &= 0xffff0000u;
-          if (kbase + 3 >= n_keys) v.y &= 0x0000ffffu;
-          vraw[t][dt] = v;
-        }
-      }
-    }
-    // mask and online softmax: the query row is lane%16, its 32 keys are spread over the 4 lane groups
-    float sv[8];
-    float mx = kNegBig;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = step * 32 + t * 16 + g * 4 + i;
-        const float v = (key <= limit) ? sacc[t][i] * scale_log2 : kNegBig;
-        sv[t * 4 + i] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float corr = exp2f(m_run - m_new);
-    float sum = 0.f;
+    // online softmax: the query row is lane%16, its 32 keys are spread over the 4 lane groups
     float p[8];
+    float corr;
+    if (step * 32 + 31 <= L) {
+      // every key of the step is visible to every valid row: no masks
+      float mx = fmaxf(fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3])),
+                       fmaxf(fmaxf(sacc[1][0], sacc[1][1]), fmaxf(sacc[1][2], sacc[1][3])));
+      mx = rows_max(mx);
+      const float m_new = fmaxf(m_run, mx * scale_log2);
+      corr = __builtin_amdgcn_exp2f(m_run - m_new);
+      float sum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      p[e] = (sv[e] > kNegBig) ? exp2f(sv[e] - m_new) : 0.f;
-      sum += p[e];
+      for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(fmaf(sacc[e >> 2][e & 3], scale_log2, -m_new));
+        sum += p[e];
+      }
+      l_run = l_run * corr + rows_sum(sum);
+      m_run = m_new;
+    } else {
+      float sv[8];
+      float mx = kNegBig;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int key = step * 32 + (e >> 2) * 16 + g * 4 + (e & 3);
+        sv[e] = key <= limit ? sacc[e >> 2][e & 3] * scale_log2 : kNegBig;
+        mx = fmaxf(mx, sv[e]);
+      }
+      mx = rows_max(mx);
+      const float m_new = fmaxf(m_run, mx);
+      corr = __builtin_amdgcn_exp2f(m_run - m_new);
+      float sum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = (sv[e] > kNegBig) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
+        sum += p[e];
+      }
+      l_run = l_run * corr + rows_sum(sum);
+      m_run = m_new;
     }
-    sum += __shfl_xor(sum, 16);
-    sum += __shfl_xor(sum, 32);
-    l_run = l_run * corr + sum;
-    m_run = m_new;
     // P enters the second product as a sum of two bf16 terms (value and rounding remainder), so
     // the product sees 16 mantissa bits of P instead of 8
-    float plo[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) plo[e] = p[e] - bf16_to_float(float_to_bf16(p[e]));
     uint4 packed, packed_lo;
     packed.x = pack_bf16x2(p[0], p[1]);
     packed.y = pack_bf16x2(p[2], p[3]);
     packed.z = pack_bf16x2(p[4], p[5]);
     packed.w = pack_bf16x2(p[6], p[7]);
-    packed_lo.x = pack_bf16x2(plo[0], plo[1]);
-    packed_lo.y = pack_bf16x2(plo[2], plo[3]);
-    packed_lo.z = pack_bf16x2(plo[4], plo[5]);
-    packed_lo.w = pack_bf16x2(plo[6], plo[7]);
+    packed_lo.x = pack_bf16x2(p[0] - __uint_as_float(packed.x << 16), p[1] - __uint_as_float(packed.x & 0xffff0000u));
+    packed_lo.y = pack_bf16x2(p[2] - __uint_as_float(packed.y << 16), p[3] - __uint_as_float(packed.y & 0xffff0000u));
+    packed_lo.z = pack_bf16x2(p[4] - __uint_as_float(packed.z << 16), p[5] - __uint_as_float(packed.z & 0xffff0000u));
+    packed_lo.w = pack_bf16x2(p[6] - __uint_as_float(packed.w << 16), p[7] - __uint_as_float(packed.w & 0xffff0000u));
     const bf16x8_t pf = *reinterpret_cast<const bf16x8_t*>(&packed);
     const bf16x8_t pf_lo = *reinterpret_cast<const bf16x8_t*>(&packed_lo);
-    // the output accumulators hold query rows g*4 + i; their rescale factor sits in lane g*4 + i
-    float f[4];
+    // the output accumulators hold query rows g*4 + i; their rescale factor sits in lane g*4 + i.
+    // Once the running maxima have settled every factor is exactly 1 and the rescale is skipped.
+    if (__any(corr != 1.0f)) {
+      float f[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) f[i] = __shfl(corr, g * 4 + i);
+      for (int i = 0; i < 4; ++i) f[i] = __shfl(corr, g * 4 + i);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) oacc[dt][i] *= f[i];
+    }
     // second product O += P V
+    const unsigned char* vb = base + 2 * PART + (c * 16 + g * 4) * 2;
+    uint2 v0[DT], v1[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
+      v0[dt] = *reinterpret_cast<const uint2*>(vb + dt * 512);
+      v1[dt] = *reinterpret_cast<const uint2*>(vb + PART + dt * 512);
+    }
+    if (step * 32 + 32 > n_keys) {
+      // keys past the end of the sequence inside the last page hold stale data, so their V is
+      // zeroed (P is 0 there, but 0 * NaN would not be)
+      const int kb0 = step * 32 + g * 4, kb1 = kb0 + 16;
+      uint2 keep0, keep1;
+      keep0.x = (kb0 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 1 < n_keys ? 0xffff0000u : 0u);
+      keep0.y = (kb0 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 3 < n_keys ? 0xffff0000u : 0u);
+      keep1.x = (kb1 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 1 < n_keys ? 0xffff0000u : 0u);
+      keep1.y = (kb1 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 3 < n_keys ? 0xffff0000u : 0u);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) oacc[dt][i] *= f[i];
-      uint4 vv = make_uint4(vraw[0][dt].x, vraw[0][dt].y, vraw[1][dt].x, vraw[1][dt].y);
+      for (int dt = 0; dt < DT; ++dt) {
+        v0[dt].x &= keep0.x; v0[dt].y &= keep0.y;
+        v1[dt].x &= keep1.x; v1[dt].y &= keep1.y;
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const uint4 vv = make_uint4(v0[dt].x, v0[dt].y, v1[dt].x, v1[dt].y);
       const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv);
       oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, vf, oacc[dt], 0, 0, 0);
       oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_lo, vf, oacc[dt], 0, 0, 0);
     }
   }
 
-  // this split's partial result for the tile's rows
+  // ---- this split's partial result for the tile's rows
+  if (!has_rows) return;
   if (g == 0 && my_ok) {
-    const size_t idx = ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * n_splits + split;
+    const size_t idx = ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * max_splits + split;
     partial_ml[idx * 2 + 0] = m_run;
     partial_ml[idx * 2 + 1] = l_run;
   }
@@ -284,60 +378,80 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const bf16_t* __restrict
     if (lrow < rows) {
       const int lr = tile_row0 + lrow;
       const int j = lr / G, hg = lr - j * G;
-      float* dst = partial_o + (((size_t)(row0 + j) * n_heads + kh * G + hg) * n_splits + split) * HD;
+      float* dst = partial_o + (((size_t)(row0 + j) * n_heads + kh * G + hg) * max_splits + split) * HD;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) dst[dt * 16 + c] = oacc[dt][i];
     }
   }
 }
 
-// attn_out[r][h*HD + d] = sum_s o_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M).  grid (R*H), block HD.
+// attn_out[r][h*HD + d] = sum_s o_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M) over the row's server's own
+// splits.  grid (R*H), block HD.
 template <int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const float* __restrict__ partial_ml,
-                                    int n_splits, bf16_t* __restrict__ attn_out) {
+                                    int max_splits, int steps_per_split, const int* __restrict__ cu_rows,
+                                    const int* __restrict__ ctx_len, int n_servers, int n_heads,
+                                    bf16_t* __restrict__ attn_out) {
   const size_t rh = blockIdx.x;
   const int d = threadIdx.x;
+  const int r = (int)(rh / n_heads);
+  const int srv = server_of_row(cu_rows, n_servers, r);
+  const int n_keys = ctx_len[srv] + (cu_rows[srv + 1] - cu_rows[srv]);
+  const int n_splits = (((n_keys + 31) >> 5) + steps_per_split - 1) / steps_per_split;
   float M = kNegBig;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, partial_ml[(rh * n_splits + s) * 2]);
-  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, partial_ml[(rh * max_splits + s) * 2]);
+  float Lsum = 0.f, acc = 0.f;
   for (int s = 0; s < n_splits; ++s) {
-    const float f = exp2f(partial_ml[(rh * n_splits + s) * 2] - M);
-    L += partial_ml[(rh * n_splits + s) * 2 + 1] * f;
-    acc += partial_o[(rh * n_splits + s) * HD + d] * f;
+    const float f = exp2f(partial_ml[(rh * max_splits + s) * 2] - M);
+    Lsum += partial_ml[(rh * max_splits + s) * 2 + 1] * f;
+    acc += partial_o[(rh * max_splits + s) * HD + d] * f;
   }
-  attn_out[rh * HD + d] = float_to_bf16(acc / L);
+  attn_out[rh * HD + d] = float_to_bf16(acc / Lsum);
 }
 
 }  // namespace
 
-// Splits of the KV range per (server, KV head) so that the grid fills the chip.
-int attention_splits(int n_servers, int n_kv, int max_ctx) {
-  const int pairs = n_servers * n_kv;
-  int want = ceil_div(512, pairs > 0 ? pairs : 1);
-  int max_s = ceil_div(max_ctx, 256);      // at least 256 keys (8 steps, 2 per wave) per split
-  int s = want < max_s ? want : max_s;
-  if (s < 1) s = 1;
-  if (s > 64) s = 64;
-  return s;
+// KV steps (32 keys) per workgroup, and the resulting largest split count, for a batch with
+// total_steps steps summed over servers and max_steps on its longest server.
+void attention_plan(int n_kv, long total_steps, int max_steps, int* steps_per_split, int* max_splits) {
+  const long want_wgs = GS_ATTN_WGS;
+  long sps = (total_steps * n_kv + want_wgs - 1) / want_wgs;
+  const long lo = (max_steps + 31) / 32 > 4 ? (max_steps + 31) / 32 : 4;   // at most 32 splits, at least 4 steps
+  if (sps < lo) sps = lo;
+  if (sps > max_steps) sps = max_steps > 0 ? max_steps : 1;
+  *steps_per_split = (int)sps;
+  *max_splits = (int)((max_steps + sps - 1) / sps);
 }
 
-size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int n_splits) {
-  return (size_t)n_rows * n_heads * n_splits * (hd + 2);
+size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits) {
+  return (size_t)n_rows * n_heads * max_splits * (hd + 2);
 }
 
 template <int HD, int G>
 static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf16_t* v_pages, const int* block_table,
                                int max_blocks, const int* cu_rows, const int* ctx_len, int n_servers, int page_size,
-                               int n_heads, int n_kv, int max_block_tokens, int n_splits, float* po, float* pml,
-                               hipStream_t stream) {
+                               int n_heads, int n_kv, int max_block_tokens, int steps_per_split, int max_splits,
+                               float* po, float* pml, hipStream_t stream) {
   const int tiles = ceil_div(max_block_tokens * G, 16);
-  dim3 grid(n_splits, n_kv, n_servers);
+  dim3 grid(max_splits, n_kv, n_servers);
   for (int t0 = 0; t0 < tiles; t0 += 8) {      // at most 8 query tiles (waves) per workgroup
     const int waves = tiles - t0 < 8 ? tiles - t0 : 8;
-    attn_mfma_kernel<HD, G><<<grid, 64 * waves, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,
-                                                             ctx_len, page_size, n_heads, n_kv, n_splits, t0 * 16, po,
-                                                             pml);
-    GS_LAUNCH_CHECK("attn_mfma");
+#define GS_RING(NW_)                                                                                              \
+  attn_ring_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks,    \
+                                                                 cu_rows, ctx_len, page_size, n_heads, n_kv,      \
+                                                                 steps_per_split, max_splits, t0 * 16, po, pml)
+    switch (waves) {
+      case 1: GS_RING(1); break;
+      case 2: GS_RING(2); break;
+      case 3: GS_RING(3); break;
+      case 4: GS_RING(4); break;
+      case 5: GS_RING(5); break;
+      case 6: GS_RING(6); break;
+      case 7: GS_RING(7); break;
+      default: GS_RING(8); break;
+    }
+#undef GS_RING
+    GS_LAUNCH_CHECK("attn_ring");
   }
   return GS_OK;
 }
@@ -346,7 +460,8 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
-                           int max_block_tokens, int n_splits, float* scratch, void* attn_out, hipStream_t stream) {
+                           int max_block_tokens, int steps_per_split, int max_splits, float* scratch, void* attn_out,
+                           hipStream_t stream) {
   if (dtype == GS_F32) {
     dim3 grid(n_rows, n_heads);
     const float* qf = static_cast<const float*>(q);
@@ -366,21 +481,25 @@ gs_status launch_attention(int dtype, const void* q, const void* k_pages, const 
   const bf16_t* kb = static_cast<const bf16_t*>(k_pages);
   const bf16_t* vb = static_cast<const bf16_t*>(v_pages);
   float* po = scratch;
-  float* pml = scratch + (size_t)n_rows * n_heads * n_splits * hd;
+  float* pml = scratch + (size_t)n_rows * n_heads * max_splits * hd;
   const int G = n_heads / n_kv;
   gs_status st = GS_OK;
 #define GS_ATTN_CASE(HD_, G_)                                                                                     \
   if (hd == HD_ && G == G_)                                                                                       \
     st = launch_mfma_g<HD_, G_>(qb, kb, vb, block_table, max_blocks, cu_rows, ctx_len, n_servers, page_size,     \
-                                n_heads, n_kv, max_block_tokens, n_splits, po, pml, stream);
+                                n_heads, n_kv, max_block_tokens, steps_per_split, max_splits, po, pml, stream);
   GS_ATTN_CASE(128, 1) GS_ATTN_CASE(128, 2) GS_ATTN_CASE(128, 4) GS_ATTN_CASE(128, 8)
   GS_ATTN_CASE(64, 1) GS_ATTN_CASE(64, 2) GS_ATTN_CASE(64, 4) GS_ATTN_CASE(64, 8)
 #undef GS_ATTN_CASE
   if (st != GS_OK) return st;
   if (hd == 128)
-    attn_combine_kernel<128><<<n_rows * n_heads, 128, 0, stream>>>(po, pml, n_splits, static_cast<bf16_t*>(attn_out));
+    attn_combine_kernel<128><<<n_rows * n_heads, 128, 0, stream>>>(po, pml, max_splits, steps_per_split, cu_rows,
+                                                                   ctx_len, n_servers, n_heads,
+                                                                   static_cast<bf16_t*>(attn_out));
   else
-    attn_combine_kernel<64><<<n_rows * n_heads, 64, 0, stream>>>(po, pml, n_splits, static_cast<bf16_t*>(attn_out));
+    attn_combine_kernel<64><<<n_rows * n_heads, 64, 0, stream>>>(po, pml, max_splits, steps_per_split, cu_rows,
+                                                                 ctx_len, n_servers, n_heads,
+                                                                 static_cast<bf16_t*>(attn_out));
   GS_LAUNCH_CHECK("attn_combine");
   return GS_OK;
 }

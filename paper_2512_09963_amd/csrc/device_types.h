@@ -12,17 +12,18 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
 
 __device__ __forceinline__ float bf16_to_float(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ bf16_t float_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+typedef __bf16 bf16x2_native_t __attribute__((ext_vector_type(2)));
+typedef float float2_native_t __attribute__((ext_vector_type(2)));
+
+// two floats -> two bfloat16 in one 32-bit word (low half first); round to nearest, ties to even
+// (the hardware packed conversion of gfx950)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const float2_native_t v = {lo, hi};
+  const bf16x2_native_t b = __builtin_convertvector(v, bf16x2_native_t);
+  return *reinterpret_cast<const uint32_t*>(&b);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
-}
+__device__ __forceinline__ bf16_t float_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 template <typename T> struct Storage;
 template <> struct Storage<float> {

@@ -21,12 +21,13 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream);
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
-int attention_splits(int n_servers, int n_kv, int max_ctx);
-size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int n_splits);
+void attention_plan(int n_kv, long total_steps, int max_steps, int* steps_per_split, int* max_splits);
+size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits);
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
-                           int max_block_tokens, int n_splits, float* scratch, void* attn_out, hipStream_t stream);
+                           int max_block_tokens, int steps_per_split, int max_splits, float* scratch, void* attn_out,
+                           hipStream_t stream);
 gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
                         const float* q_probs, const int* draft_tokens, const float* u_accept,
                         const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream);
@@ -94,9 +95,10 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   p.q = c.take<char>(R * hq * ctx->elem);
   p.attn = c.take<char>(R * hq * ctx->elem);
   p.act = c.take<char>(R * m.d_ffn * ctx->elem);
-  int max_splits = 1;
-  for (int n = 1; n <= max_servers; ++n)
-    max_splits = std::max(max_splits, gs::attention_splits(n, m.n_kv_heads, max_ctx));
+  // the planner never uses more than 32 splits per server and never fewer than 4 steps per split
+  const int max_steps = (max_ctx + 31) / 32;
+  const int max_splits = std::max(1, std::min(32, (max_steps + 3) / 4));
+  (void)max_servers;
   p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
   p.logits = c.take<float>(R * m.vocab);
   p.draft_tokens = c.take<int>(R);
@@ -272,7 +274,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     return gs::fail(GS_EINVAL, "invalid KV cache descriptor");
   if (m.dtype == GS_BF16 && kv->page_size % 16 != 0)
     return gs::fail(GS_ESHAPE, "bf16 attention needs a page size that is a multiple of 16");
-  long R = 0, G = 0;
+  long R = 0, G = 0, total_steps = 0;
   int max_t = 0, max_ctx = 0;
   for (int i = 0; i < n; ++i) {
     const int g = b->gamma_host[i], L = b->ctx_len_host[i];
@@ -285,6 +287,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     G += g;
     max_t = std::max(max_t, g + 1);
     max_ctx = std::max(max_ctx, L + g + 1);
+    total_steps += (L + g + 1 + 31) / 32;
   }
   if (R > (1 << 20)) return gs::fail(GS_EINVAL, "too many rows");
   const bool do_accept = b->q_probs != nullptr;
@@ -301,7 +304,8 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   const int rows = (int)R, d = m.d_model, hq = m.n_heads * m.head_dim, qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
   const int F = m.d_ffn;
   const size_t layer_stride = (size_t)kv->n_pages * m.n_kv_heads * kv->page_size * m.head_dim * ctx->elem;
-  const int attn_splits = gs::attention_splits(n, m.n_kv_heads, max_ctx);
+  int attn_sps = 1, attn_splits = 1;
+  gs::attention_plan(m.n_kv_heads, total_steps, (max_ctx + 31) / 32, &attn_sps, &attn_splits);
   gs_status st;
 #define GS_TRY(call)          \
   do {                        \
@@ -331,7 +335,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
                                   b->ctx_len, n, b->block_table, b->max_blocks, kv->page_size, m.n_heads,
                                   m.n_kv_heads, m.head_dim, m.rope_theta, p.q, kl, vl, stream));
     GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
-                                kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_splits,
+                                kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_sps, attn_splits,
                                 p.attn_scratch, p.attn, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
     GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
