@@ -135,10 +135,10 @@ typedef struct {
  * Projection matrices are logically [out_features, in_features] in the model dtype and must be
  * given in the layout gs_pack_weight produces (one-time repack at load):
  *   GS_F32 : row-major, unchanged
- *   GS_BF16: tile-packed [out/16][in/64][2][64][8]: for a tile of 16 output rows and a step of 64
+ *   GS_BF16: tile-packed [in/64][out/16][2][64][8]: for a tile of 16 output rows and a step of 64
  *            inputs, lane l = 16 g + c (c = row in tile, g = 0..3) owns inputs 16 g .. 16 g + 15 of
  *            row c, the first 8 in half 0 and the last 8 in half 1; so the 2 KB one wavefront needs
- *            per step are contiguous, and so are the steps of a tile.
+ *            per step are contiguous, and the blocks of all tiles at one step form one band.
  * The embedding table is gathered by row and stays row-major.
  */
 gs_status gs_pack_weight(const void* w_rowmajor /* dev */, void* w_packed /* dev, same size, not in place */,

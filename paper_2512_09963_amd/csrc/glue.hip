@@ -85,56 +85,57 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x
   }
 }
 
-// Sums the QKV partials, rotates Q and K at the row's position, stores Q [R][H][hd] and
-// appends K ([page][H_kv][slot][hd]) and V ([page][H_kv][hd][slot]) to the layer's pages.
-// One workgroup per row; a lane owns one rotation pair index i for several heads, so the
-// angle's sine and cosine are computed once per lane.  blockDim.x is a multiple of hd/2.
-template <typename T>
-__global__ __launch_bounds__(1024) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
-                                                           const int* __restrict__ cu_rows,
-                                                           const int* __restrict__ ctx_len, int n_servers,
-                                                           const int* __restrict__ block_table, int max_blocks,
-                                                           int page_size, int n_heads, int n_kv, int hd,
-                                                           double log2_theta, T* __restrict__ q_out,
-                                                           T* __restrict__ k_pages, T* __restrict__ v_pages) {
-  const int r = blockIdx.x;
+// Per-row facts that every layer of a step shares: where the row's K/V go (page, slot) and the
+// rotary sine/cosine of its position.  rope [R][hd/2] (cos, sin).  The angle pos * theta^(-2i/hd)
+// reaches thousands of radians: it is formed in double, so that the rotated values agree with a
+// float64 evaluation to fp32 rounding.  grid R, block hd/2.
+__global__ void row_meta_kernel(const int* __restrict__ cu_rows, const int* __restrict__ ctx_len, int n_servers,
+                                const int* __restrict__ block_table, int max_blocks, int page_size, int hd,
+                                double log2_theta, int2* __restrict__ row_slot, float2* __restrict__ rope) {
+  const int r = blockIdx.x, i = threadIdx.x;
   const int srv = server_of_row(cu_rows, n_servers, r);
   const int pos = ctx_len[srv] + (r - cu_rows[srv]);
-  const int page = block_table[(size_t)srv * max_blocks + pos / page_size];
-  const int slot = pos % page_size;
-  const int width = (n_heads + 2 * n_kv) * hd;
-  const int half = hd >> 1;
-  const size_t split_stride = (size_t)n_rows * width;
-  const float* row = qkv + (size_t)r * width;
-  auto value = [&](int col) {
-    float v0 = 0.f, v1 = 0.f;
-    int s = 0;
-    for (; s + 2 <= n_splits; s += 2) {
-      v0 += row[(size_t)s * split_stride + col];
-      v1 += row[(size_t)(s + 1) * split_stride + col];
-    }
-    if (s < n_splits) v0 += row[(size_t)s * split_stride + col];
-    return v0 + v1;
-  };
-  const int i = threadIdx.x % half, grp = threadIdx.x / half, n_grp = blockDim.x / half;
-  // the angle pos * theta^(-2i/hd) reaches thousands of radians: form it in double, so that the
-  // rotated values agree with a float64 evaluation to fp32 rounding (once per lane, not per element)
+  if (i == 0) row_slot[r] = make_int2(block_table[(size_t)srv * max_blocks + pos / page_size], pos % page_size);
   const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
-  double sn_d, cs_d;
-  sincos((double)pos * inv_freq, &sn_d, &cs_d);
-  const float sn = (float)sn_d, cs = (float)cs_d;
-  for (int head = grp; head < n_heads + n_kv; head += n_grp) {
-    const float a = value(head * hd + i), b = value(head * hd + i + half);
-    const float ra = a * cs - b * sn, rb = b * cs + a * sn;
+  double sn, cs;
+  sincos((double)pos * inv_freq, &sn, &cs);
+  rope[(size_t)r * (hd >> 1) + i] = make_float2((float)cs, (float)sn);
+}
+
+// Sums the QKV partials, rotates Q and K at the row's position, stores Q [R][H][hd] and
+// appends K ([page][H_kv][slot][hd]) and V ([page][H_kv][hd][slot]) to the layer's pages.
+// grid (R, (H + 2 H_kv) * hd/2 / 256): a thread owns the element pair (i, i + hd/2) of one head.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
+                                                          const int2* __restrict__ row_slot,
+                                                          const float2* __restrict__ rope, int page_size,
+                                                          int n_heads, int n_kv, int hd, T* __restrict__ q_out,
+                                                          T* __restrict__ k_pages, T* __restrict__ v_pages) {
+  const int r = blockIdx.x;
+  const int half = hd >> 1;
+  const int item = blockIdx.y * 256 + threadIdx.x;
+  const int head = item / half, i = item - head * half;
+  if (head >= n_heads + 2 * n_kv) return;
+  const int width = (n_heads + 2 * n_kv) * hd;
+  const size_t split_stride = (size_t)n_rows * width;
+  const float* src = qkv + (size_t)r * width + head * hd + i;
+  float a = 0.f, b = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    a += src[(size_t)s * split_stride];
+    b += src[(size_t)s * split_stride + half];
+  }
+  const int2 ps = row_slot[r];
+  if (head < n_heads + n_kv) {
+    const float2 cs = rope[(size_t)r * half + i];
+    const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
     T* dst = (head < n_heads) ? q_out + ((size_t)r * n_heads + head) * hd
-                              : k_pages + (((size_t)page * n_kv + (head - n_heads)) * page_size + slot) * hd;
+                              : k_pages + (((size_t)ps.x * n_kv + (head - n_heads)) * page_size + ps.y) * hd;
     Storage<T>::store(dst + i, ra);
     Storage<T>::store(dst + i + half, rb);
-  }
-  const int v_col0 = (n_heads + n_kv) * hd;
-  for (int e = threadIdx.x; e < n_kv * hd; e += blockDim.x) {
-    const int kh = e / hd, dd = e - kh * hd;
-    Storage<T>::store(v_pages + (((size_t)page * n_kv + kh) * hd + dd) * page_size + slot, value(v_col0 + e));
+  } else {
+    T* dst = v_pages + ((size_t)ps.x * n_kv + (head - n_heads - n_kv)) * hd * page_size + ps.y;
+    Storage<T>::store(dst + (size_t)i * page_size, a);
+    Storage<T>::store(dst + (size_t)(i + half) * page_size, b);
   }
 }
 
@@ -182,18 +183,24 @@ gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_sp
   return GS_OK;
 }
 
-gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const int* cu_rows,
-                             const int* ctx_len, int n_servers, const int* block_table, int max_blocks,
-                             int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
+gs_status launch_row_meta(const int* cu_rows, const int* ctx_len, int n_servers, int n_rows, const int* block_table,
+                          int max_blocks, int page_size, int hd, float rope_theta, void* row_slot, void* rope,
+                          hipStream_t stream) {
+  row_meta_kernel<<<n_rows, hd / 2, 0, stream>>>(cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size, hd,
+                                                 log2((double)rope_theta), static_cast<int2*>(row_slot),
+                                                 static_cast<float2*>(rope));
+  GS_LAUNCH_CHECK("row_meta");
+  return GS_OK;
+}
+
+gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const void* row_slot,
+                             const void* rope, int page_size, int n_heads, int n_kv, int hd, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream) {
-  const double log2_theta = log2((double)rope_theta);
-  const int half = hd / 2;
-  int groups = (n_heads + n_kv) < 1024 / half ? (n_heads + n_kv) : 1024 / half;
-  const int threads = ceil_div(groups * half, 64) * 64 / half * half;   // multiple of 64 and of hd/2 (hd is 64 or 128)
-  GS_DISPATCH_T(dtype, rope_append_kernel<T><<<n_rows, threads, 0, stream>>>(
-                           qkv, n_splits, n_rows, cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size,
-                           n_heads, n_kv, hd, log2_theta, static_cast<T*>(q_out), static_cast<T*>(k_pages),
-                           static_cast<T*>(v_pages));)
+  const dim3 grid(n_rows, ceil_div((n_heads + 2 * n_kv) * (hd / 2), 256));
+  GS_DISPATCH_T(dtype, rope_append_kernel<T><<<grid, 256, 0, stream>>>(
+                           qkv, n_splits, n_rows, static_cast<const int2*>(row_slot),
+                           static_cast<const float2*>(rope), page_size, n_heads, n_kv, hd, static_cast<T*>(q_out),
+                           static_cast<T*>(k_pages), static_cast<T*>(v_pages));)
   GS_LAUNCH_CHECK("rope_append");
   return GS_OK;
 }

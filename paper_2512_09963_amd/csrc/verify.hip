@@ -16,9 +16,11 @@ gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, 
 gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
                              float eps, void* h, int d, hipStream_t stream);
-gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const int* cu_rows,
-                             const int* ctx_len, int n_servers, const int* block_table, int max_blocks,
-                             int page_size, int n_heads, int n_kv, int hd, float rope_theta, void* q_out,
+gs_status launch_row_meta(const int* cu_rows, const int* ctx_len, int n_servers, int n_rows, const int* block_table,
+                          int max_blocks, int page_size, int hd, float rope_theta, void* row_slot, void* rope,
+                          hipStream_t stream);
+gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_rows, const void* row_slot,
+                             const void* rope, int page_size, int n_heads, int n_kv, int hd, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream);
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
 void attention_plan(int n_kv, long total_steps, int max_steps, int* steps_per_split, int* max_splits);
@@ -63,6 +65,8 @@ struct Plan {
   float* attn_scratch;
   float* logits;
   int* draft_tokens;
+  void* row_slot;   // [R] (page, slot) of the row's own K/V
+  void* rope;       // [R][hd/2] (cos, sin)
   void* accept_ws;
   size_t bytes;
 };
@@ -102,6 +106,8 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
   p.logits = c.take<float>(R * m.vocab);
   p.draft_tokens = c.take<int>(R);
+  p.row_slot = c.take<int>(2 * R);
+  p.rope = c.take<float>(R * m.head_dim);
   size_t acc = 0;
   for (int n = 1; n <= max_servers; ++n) acc = std::max(acc, gs::accept_workspace_bytes(n, max_rows, m.vocab));
   p.accept_ws = c.take<char>(acc);
@@ -321,6 +327,8 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     GS_TRY(timer.end());        \
   } while (0)
   GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(m.dtype, ctx->embed, b->tokens, p.x, rows, d, stream));
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_row_meta(b->cu_rows, b->ctx_len, n, rows, b->block_table, b->max_blocks, kv->page_size,
+                                              m.head_dim, m.rope_theta, p.row_slot, p.rope, stream));
   const float* pending = nullptr;   // split-K partials of the projection whose result is still to be added to x
   int pending_splits = 0;
   for (int l = 0; l < m.n_layers; ++l) {
@@ -331,9 +339,8 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
     char* kl = static_cast<char*>(kv->k_pages) + layer_stride * l;
     char* vl = static_cast<char*>(kv->v_pages) + layer_stride * l;
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, b->cu_rows,
-                                  b->ctx_len, n, b->block_table, b->max_blocks, kv->page_size, m.n_heads,
-                                  m.n_kv_heads, m.head_dim, m.rope_theta, p.q, kl, vl, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, p.row_slot,
+                                  p.rope, kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, p.q, kl, vl, stream));
     GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
                                 kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_sps, attn_splits,
                                 p.attn_scratch, p.attn, stream));
