@@ -145,6 +145,11 @@ def test_bf16_page_size_64_and_single_server():
     _run_case(ms, 79, np.array([8], np.int32), np.array([700], np.int32), 64, std=0.08)
 
 
+def test_bf16_page_size_48_not_a_power_of_two():
+    ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
+    _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
+
+
 def test_verify_batch_rejects_bad_descriptors():
     import torch
     from paper_2512_09963_amd import binding as gsb, workload as wl
