@@ -34,19 +34,18 @@ namespace {
 #ifndef GS_GEMM_WGS
 #define GS_GEMM_WGS 512
 #endif
-constexpr int kGemmThreads = 256;
 constexpr int kBK = 64;           // k elements per step
 constexpr int kLdsRow = kBK + 8;  // padded LDS row (bf16 elements): 144 bytes
 
-template <int MT, int DEPTH>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf16_t* __restrict__ X,
+template <int MT, int DEPTH, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t* __restrict__ X,
                                                                         const bf16_t* __restrict__ Wp,
                                                                         float* __restrict__ P, int M, int N, int K,
                                                                         int k_per_split) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
-  const int n_tile = blockIdx.x * 4 + wave;
+  const int n_tile = blockIdx.x * NW + wave;
   const int n0 = n_tile * 16;
   const int split = blockIdx.y;
   const int m0 = blockIdx.z * (MT * 16);
@@ -56,6 +55,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_skinny_kernel(const bf
 
   // activation tile: MT*16 rows x 64 k = MT*128 chunks of 16 bytes
   constexpr int kChunks = MT * 128;
+  constexpr int kGemmThreads = 64 * NW;
   constexpr int kPasses = (kChunks + kGemmThreads - 1) / kGemmThreads;
   uint4 xreg[DEPTH][kPasses];
   auto load_x = [&](int slot, int step) {
@@ -203,10 +203,15 @@ gs_status launch_pack_weight(const void* src, void* dst, int N, int K, hipStream
   return GS_OK;
 }
 
+// Waves per workgroup: wide matrices get 8 (128 columns per workgroup), which halves the number of
+// times the activation rows are re-read from L2; narrower ones keep 4 so that the launch still has
+// enough workgroups.
+static int gemm_waves(int N) { return (N % 128 == 0 && N / 128 >= 192) ? 8 : 4; }
+
 // Number of K splits the bf16 kernel will use for this shape (1 for fp32).
 int gemm_splits(int dtype, int M, int N, int K) {
   if (dtype != GS_BF16) return 1;
-  const int n_blocks = N / 64;
+  const int n_blocks = N / (16 * gemm_waves(N));
   const int m_chunks = ceil_div(M, 128);
   int want = (GS_GEMM_WGS + n_blocks * m_chunks / 2) / (n_blocks * m_chunks);   // about two workgroups per CU
   int max_s = K / 512 > 0 ? K / 512 : 1;                                // at least 8 steps per split
@@ -214,6 +219,23 @@ int gemm_splits(int dtype, int M, int N, int K) {
   if (s < 1) s = 1;
   const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
   return ceil_div(K, k_per);
+}
+
+template <int NW>
+static void launch_skinny(const bf16_t* x, const bf16_t* w, float* P, int M, int N, int K, int s, int k_per,
+                          hipStream_t stream) {
+  const int tiles = ceil_div(M, 16);
+  const dim3 grid(N / (16 * NW), s, 1);
+  if (tiles <= 1) {
+    gemm_bf16_skinny_kernel<1, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
+  } else if (tiles <= 2) {
+    gemm_bf16_skinny_kernel<2, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
+  } else if (tiles <= 4) {
+    gemm_bf16_skinny_kernel<4, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
+  } else {
+    gemm_bf16_skinny_kernel<8, GS_GEMM_DEPTH, NW>
+        <<<dim3(grid.x, s, ceil_div(M, 128)), 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
+  }
 }
 
 // P [splits][M][N] fp32 partial sums of X [M][K] * W[N][K]^T (W tile-packed for bf16, row-major for fp32).
@@ -224,17 +246,8 @@ gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, 
     const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
     const bf16_t* x = static_cast<const bf16_t*>(X);
     const bf16_t* w = static_cast<const bf16_t*>(W);
-    const int tiles = ceil_div(M, 16);
-    if (tiles <= 1) {
-      gemm_bf16_skinny_kernel<1, GS_GEMM_DEPTH><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
-    } else if (tiles <= 2) {
-      gemm_bf16_skinny_kernel<2, GS_GEMM_DEPTH><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
-    } else if (tiles <= 4) {
-      gemm_bf16_skinny_kernel<4, GS_GEMM_DEPTH><<<dim3(N / 64, s, 1), kGemmThreads, 0, stream>>>(x, w, P, M, N, K, k_per);
-    } else {
-      gemm_bf16_skinny_kernel<8, GS_GEMM_DEPTH><<<dim3(N / 64, s, ceil_div(M, 128)), kGemmThreads, 0, stream>>>(x, w, P, M, N, K,
-                                                                                                   k_per);
-    }
+    if (gemm_waves(N) == 8) launch_skinny<8>(x, w, P, M, N, K, s, k_per, stream);
+    else launch_skinny<4>(x, w, P, M, N, K, s, k_per, stream);
     GS_LAUNCH_CHECK("gemm_bf16_skinny");
   } else {
     gemm_f32_kernel<<<dim3(ceil_div(N, 64), ceil_div(M, 64)), 256, 0, stream>>>(
