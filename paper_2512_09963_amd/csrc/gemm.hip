@@ -39,16 +39,27 @@ constexpr int kLdsRow = kBK + 8;  // padded LDS row (bf16 elements): 144 bytes
 
 template <int MT, int DEPTH, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t* __restrict__ X,
-                                                                        const bf16_t* __restrict__ Wp,
-                                                                        float* __restrict__ P, int M, int N, int K,
-                                                                        int k_per_split) {
+                                                                   const bf16_t* __restrict__ Wp,
+                                                                   float* __restrict__ P, int M, int N, int K,
+                                                                   int k_per_split, int m_chunks) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
-  const int n_tile = blockIdx.x * NW + wave;
+  // More rows than one workgroup takes (MT * 16): the row chunks of one column block are separate
+  // workgroups that read the same weights.  Workgroups are handed to the 8 XCDs round robin by
+  // their linear index, so the chunks of a column block get indices that are 8 apart: they land on
+  // the same XCD one after the other, and all but the first read the weights from that XCD's L2.
+  int n_block = blockIdx.x, m_chunk = 0;
+  if (m_chunks > 1) {
+    const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
+    m_chunk = t % m_chunks;
+    n_block = (t / m_chunks) * 8 + xcd;
+    if (n_block * (16 * NW) >= N) return;      // padding of the grid to a multiple of 8 column blocks
+  }
+  const int n_tile = n_block * NW + wave;
   const int n0 = n_tile * 16;
   const int split = blockIdx.y;
-  const int m0 = blockIdx.z * (MT * 16);
+  const int m0 = m_chunk * (MT * 16);
   const int k_begin = split * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
   const int n_steps = (k_end - k_begin) / kBK;
@@ -138,6 +149,122 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
   }
 }
 
+// More than 64 rows (a few hundred per step with tens of draft servers): the same streaming design
+// with a taller and wider wave tile.  A wave owns 32 output columns (two column tiles) and all
+// MT * 16 rows of its row chunk, so every activation fragment read from LDS feeds two MFMAs and every
+// weight fragment MT of them; a workgroup covers 128 columns.  Row chunks of one column block are
+// separate workgroups that read the same weights: workgroups are handed to the 8 XCDs round robin by
+// their linear index, so the chunks of a column block get indices that are 8 apart and land on the
+// same XCD one after the other, and all but the first find the weights in that XCD's L2.
+// grid (ceil(N/128 / 8) * 8 * m_chunks, S).
+template <int MT>
+__global__ __launch_bounds__(256) void gemm_bf16_tall_kernel(const bf16_t* __restrict__ X,
+                                                             const bf16_t* __restrict__ Wp, float* __restrict__ P,
+                                                             int M, int N, int K, int k_per_split, int m_chunks) {
+  constexpr int NT = 2, DEPTH = 2;
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
+  const int m_chunk = t % m_chunks;
+  const int n_block = (t / m_chunks) * 8 + xcd;
+  if (n_block * (64 * NT) >= N) return;        // padding of the grid to a multiple of 8 column blocks
+  const int n_tile0 = (n_block * 4 + wave) * NT;
+  const int split = blockIdx.y;
+  const int m0 = m_chunk * (MT * 16);
+  const int k_begin = split * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  const int n_steps = (k_end - k_begin) / kBK;
+
+  constexpr int kChunks = MT * 128;
+  constexpr int kPasses = (kChunks + 255) / 256;
+  uint4 xreg[DEPTH][kPasses];
+  auto load_x = [&](int slot, int step) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * 256;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ch < kChunks && m0 + row < M)
+        v = *reinterpret_cast<const uint4*>(X + (size_t)(m0 + row) * K + k_begin + step * kBK + col);
+      xreg[slot][p] = v;
+    }
+  };
+  auto store_x = [&](int buf, int slot) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * 256;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[slot][p];
+    }
+  };
+  const size_t w_step_stride = (size_t)(N / 16) * 128;
+  const uint4* wbase = reinterpret_cast<const uint4*>(Wp) + (size_t)(k_begin / kBK) * w_step_stride + (size_t)n_tile0 * 128 + lane;
+  uint4 wreg[DEPTH][NT][2];
+  auto load_w = [&](int slot, int step) {
+    const uint4* p = wbase + (size_t)step * w_step_stride;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      wreg[slot][nt][0] = p[nt * 128];
+      wreg[slot][nt][1] = p[nt * 128 + 64];
+    }
+  };
+
+  floatx4_t acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < n_steps) {
+      load_w(d, d);
+      load_x(d, d);
+    }
+  for (int base = 0; base < n_steps; base += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int step = base + d;
+      if (step < n_steps) {
+        const int buf = step & 1;
+        store_x(buf, d);
+        __syncthreads();
+        if (step + DEPTH < n_steps) load_x(d, step + DEPTH);
+        bf16x8_t b[NT][2];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          b[nt][0] = *reinterpret_cast<const bf16x8_t*>(&wreg[d][nt][0]);
+          b[nt][1] = *reinterpret_cast<const bf16x8_t*>(&wreg[d][nt][1]);
+        }
+        if (step + DEPTH < n_steps) load_w(d, step + DEPTH);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const bf16_t* ap = &xs[buf][(mt * 16 + c) * kLdsRow + g * 16];
+          const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(ap);
+          const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(ap + 8);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b[nt][0], acc[mt][nt], 0, 0, 0);
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b[nt][1], acc[mt][nt], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  float* out = P + (size_t)split * M * N;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = m0 + mt * 16 + g * 4 + i;
+      if (row < M) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) out[(size_t)row * N + (n_tile0 + nt) * 16 + c] = acc[mt][nt][i];
+      }
+    }
+}
+
 // fp32: 64x64 output tile, k step 16, each of 256 threads owns a 4x4 block.
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ X, const float* __restrict__ W,
                                                        float* __restrict__ Y, int M, int N, int K) {
@@ -203,38 +330,75 @@ gs_status launch_pack_weight(const void* src, void* dst, int N, int K, hipStream
   return GS_OK;
 }
 
-// Waves per workgroup: wide matrices get 8 (128 columns per workgroup), which halves the number of
-// times the activation rows are re-read from L2; narrower ones keep 4 so that the launch still has
-// enough workgroups.
-static int gemm_waves(int N) { return (N % 128 == 0 && N / 128 >= 192) ? 8 : 4; }
+// Which bf16 kernel serves a shape, and how the launch is cut.
+struct GemmPlan {
+  bool tall;      // gemm_bf16_tall_kernel (more than 64 rows, N a multiple of 128)
+  int waves;      // skinny: waves per workgroup (4 or 8)
+  int mt;         // row tiles per workgroup
+  int m_chunks;   // row chunks (separate workgroups)
+  int splits;     // K splits
+  int k_per;      // k elements per split (multiple of 64)
+};
+
+static GemmPlan gemm_plan(int M, int N, int K) {
+  GemmPlan p;
+  const int tiles = ceil_div(M, 16);
+  p.tall = tiles > 4 && N % 128 == 0;
+  int n_blocks;
+  if (p.tall) {
+    p.waves = 4;
+    p.m_chunks = ceil_div(tiles, 10);
+    const int per = ceil_div(tiles, p.m_chunks);      // 3 .. 10 row tiles per chunk
+    p.mt = per <= 6 ? 6 : per <= 8 ? 8 : 10;
+    p.m_chunks = ceil_div(tiles, p.mt);
+    n_blocks = N / 128;
+  } else {
+    // wide matrices get 8 waves (128 columns per workgroup), which halves the number of times the
+    // activation rows are re-read from L2; narrower ones keep 4 so that the launch still has
+    // enough workgroups
+    p.waves = (N % 128 == 0 && N / 128 >= 192) ? 8 : 4;
+    p.mt = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : 8;
+    p.m_chunks = ceil_div(tiles, p.mt);
+    n_blocks = N / (16 * p.waves);
+  }
+  const int wgs = n_blocks * p.m_chunks;
+  int want = (GS_GEMM_WGS + wgs / 2) / wgs;                // about two workgroups per CU
+  const int max_s = K / 512 > 0 ? K / 512 : 1;             // at least 8 steps per split
+  int s = want < max_s ? want : max_s;
+  if (s < 1) s = 1;
+  p.k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
+  p.splits = ceil_div(K, p.k_per);
+  return p;
+}
 
 // Number of K splits the bf16 kernel will use for this shape (1 for fp32).
 int gemm_splits(int dtype, int M, int N, int K) {
-  if (dtype != GS_BF16) return 1;
-  const int n_blocks = N / (16 * gemm_waves(N));
-  const int m_chunks = ceil_div(M, 128);
-  int want = (GS_GEMM_WGS + n_blocks * m_chunks / 2) / (n_blocks * m_chunks);   // about two workgroups per CU
-  int max_s = K / 512 > 0 ? K / 512 : 1;                                // at least 8 steps per split
-  int s = want < max_s ? want : max_s;
-  if (s < 1) s = 1;
-  const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
-  return ceil_div(K, k_per);
+  if (dtype != GS_BF16 || M <= 0) return 1;
+  return gemm_plan(M, N, K).splits;
 }
 
 template <int NW>
-static void launch_skinny(const bf16_t* x, const bf16_t* w, float* P, int M, int N, int K, int s, int k_per,
+static void launch_skinny(const GemmPlan& p, const bf16_t* x, const bf16_t* w, float* P, int M, int N, int K,
                           hipStream_t stream) {
-  const int tiles = ceil_div(M, 16);
-  const dim3 grid(N / (16 * NW), s, 1);
-  if (tiles <= 1) {
-    gemm_bf16_skinny_kernel<1, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
-  } else if (tiles <= 2) {
-    gemm_bf16_skinny_kernel<2, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
-  } else if (tiles <= 4) {
-    gemm_bf16_skinny_kernel<4, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
-  } else {
-    gemm_bf16_skinny_kernel<8, GS_GEMM_DEPTH, NW>
-        <<<dim3(grid.x, s, ceil_div(M, 128)), 64 * NW, 0, stream>>>(x, w, P, M, N, K, k_per);
+  const int n_blocks = N / (16 * NW);
+  const int gx = p.m_chunks > 1 ? ceil_div(n_blocks, 8) * 8 * p.m_chunks : n_blocks;
+  const dim3 grid(gx, p.splits, 1);
+  switch (p.mt) {
+    case 1: gemm_bf16_skinny_kernel<1, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    case 2: gemm_bf16_skinny_kernel<2, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    case 4: gemm_bf16_skinny_kernel<4, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    default:
+      gemm_bf16_skinny_kernel<8, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
+  }
+}
+
+static void launch_tall(const GemmPlan& p, const bf16_t* x, const bf16_t* w, float* P, int M, int N, int K,
+                        hipStream_t stream) {
+  const dim3 grid(ceil_div(N / 128, 8) * 8 * p.m_chunks, p.splits, 1);
+  switch (p.mt) {
+    case 6: gemm_bf16_tall_kernel<6><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
+    case 8: gemm_bf16_tall_kernel<8><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
+    default: gemm_bf16_tall_kernel<10><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
   }
 }
 
@@ -242,13 +406,13 @@ static void launch_skinny(const bf16_t* x, const bf16_t* w, float* P, int M, int
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream) {
   if (M <= 0) return GS_OK;
   if (dtype == GS_BF16) {
-    const int s = gemm_splits(dtype, M, N, K);
-    const int k_per = ceil_div(ceil_div(K, s), kBK) * kBK;
+    const GemmPlan p = gemm_plan(M, N, K);
     const bf16_t* x = static_cast<const bf16_t*>(X);
     const bf16_t* w = static_cast<const bf16_t*>(W);
-    if (gemm_waves(N) == 8) launch_skinny<8>(x, w, P, M, N, K, s, k_per, stream);
-    else launch_skinny<4>(x, w, P, M, N, K, s, k_per, stream);
-    GS_LAUNCH_CHECK("gemm_bf16_skinny");
+    if (p.tall) launch_tall(p, x, w, P, M, N, K, stream);
+    else if (p.waves == 8) launch_skinny<8>(p, x, w, P, M, N, K, stream);
+    else launch_skinny<4>(p, x, w, P, M, N, K, stream);
+    GS_LAUNCH_CHECK("gemm_bf16");
   } else {
     gemm_f32_kernel<<<dim3(ceil_div(N, 64), ceil_div(M, 64)), 256, 0, stream>>>(
         static_cast<const float*>(X), static_cast<const float*>(W), P, M, N, K);

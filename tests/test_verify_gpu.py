@@ -145,6 +145,17 @@ def test_bf16_page_size_64_and_single_server():
     _run_case(ms, 79, np.array([8], np.int32), np.array([700], np.int32), 64, std=0.08)
 
 
+@pytest.mark.parametrize("n_servers,gmax", [(10, 8), (24, 16)])
+def test_bf16_many_rows_use_the_tall_projection_kernel(n_servers, gmax):
+    # 60..250 target rows: more than one 64-row tile set, with and without row chunks
+    ms = synth.ModelShape(2, 256, 4, 2, 128, 512, 1024, 500000.0, dtype="bf16")
+    rng = np.random.default_rng(81 + n_servers)
+    gamma = rng.integers(gmax // 2, gmax + 1, n_servers).astype(np.int32)
+    ctx = rng.integers(0, 200, n_servers).astype(np.int32)
+    assert int(gamma.sum()) + n_servers > 64
+    _run_case(ms, 81, gamma, ctx, 16, std=0.08)
+
+
 def test_bf16_page_size_48_not_a_power_of_two():
     ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
