@@ -94,9 +94,6 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
   }
 }
 
-#ifndef GS_ATTN_WGS
-#define GS_ATTN_WGS 768
-#endif
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA path.  grid (max_splits, H_kv, N), NW waves per workgroup.
 //
@@ -412,11 +409,19 @@ __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const f
 }  // namespace
 
 // KV steps (32 keys) per workgroup, and the resulting largest split count, for a batch with
-// total_steps steps summed over servers and max_steps on its longest server.
-void attention_plan(int n_kv, long total_steps, int max_steps, int* steps_per_split, int* max_splits) {
-  const long want_wgs = GS_ATTN_WGS;
-  long sps = (total_steps * n_kv + want_wgs - 1) / want_wgs;
-  const long lo = (max_steps + 31) / 32 > 4 ? (max_steps + 31) / 32 : 4;   // at most 32 splits, at least 4 steps
+// total_steps steps summed over servers, max_steps on its longest server and query tiles of at most
+// max_block_tokens rows per server.  Workgroups take equally many steps, so a launch runs in rounds of
+// as many workgroups as fit the chip at once; enough rounds (4) keep the last, partly filled one cheap,
+// while a floor on the steps per workgroup bounds what the partial results cost.
+void attention_plan(int n_kv, int group, int max_block_tokens, long total_steps, int max_steps, int* steps_per_split,
+                    int* max_splits) {
+  const int tiles = ceil_div(max_block_tokens * group, 16);
+  const int waves = tiles < 8 ? (tiles > 0 ? tiles : 1) : 8;
+  const int wgs_per_cu = 16 / waves < 5 ? 16 / waves : 5;      // 16 waves by registers, 5 workgroups by LDS
+  const long slots = 256L * wgs_per_cu;
+  long sps = (total_steps * n_kv + 4 * slots - 1) / (4 * slots);
+  if (sps < 6) sps = 6;
+  const long lo = (max_steps + 31) / 32;                        // at most 32 splits per server
   if (sps < lo) sps = lo;
   if (sps > max_steps) sps = max_steps > 0 ? max_steps : 1;
   *steps_per_split = (int)sps;
