@@ -23,10 +23,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-# profiles/hbm_traffic_counters.md (121.78 MB fetched + 6.40 MB written, scaled by the copy-kernel factors
+# profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "bde3b0821217f2f3fb8f07a9e1c1f6fe1e1c1ef157a83d4e896c0388d0df94b1",
-                "bytes_per_launch": 128181401}
+GEMM_TRAFFIC = {"gemm_hip_sha256": "c4f77d8fb1bd791205f6c9178ea3e521aaf80380c9ee6f9d7221f203941cb7b8",
+                "bytes_per_launch": 129640035}
 
 
 def measured_traffic():
