@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
@@ -45,7 +46,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (result is marked invalid)")
-    ap.add_argument("--workload", choices=["cfg3", "cfg4", "cfg5"], default="cfg3",
+    ap.add_argument("--workload", choices=["cfg3", "cfg4", "cfg5", "rows1024"], default="cfg3",
                     help="cfg3 (default) is the configuration the metric is quoted on; cfg4 (32 ragged servers, "
                          "paged) and cfg5 (70B shape) are extra measurements")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -62,13 +63,17 @@ WORKLOADS = {
             "permuted 16-token KV pages",
     "cfg5": "llama3-70b-shaped verify (80 layers, d 8192, 64q/8kv heads, ffn 28672, vocab 128256), "
             "16 draft servers, gamma U[2,8], ctx 4096",
+    "rows1024": "llama3-8b-shaped verify at a compute-bound row count: 8 servers x 128-row blocks on an empty "
+                "cache (1024 target rows); not the paper's operating point, shows the projection kernel "
+                "against the MFMA peak",
 }
 
 
 def build_workload(ms, seed, name="cfg3"):
     import torch
     from paper_2512_09963_amd import synth, workload as wl
-    cfg = {"cfg3": synth.config3, "cfg4": synth.config4, "cfg5": synth.config5}[name](seed, ms)
+    cfg = {"cfg3": synth.config3, "cfg4": synth.config4, "cfg5": synth.config5,
+           "rows1024": synth.config_rows1024}[name](seed, ms)
     t0 = time.time()
     ver, kv, db = wl.upload_config(cfg, progress=True)
     torch.cuda.synchronize()
@@ -249,14 +254,20 @@ def main():
                    "n_servers": db.n_servers, "draft_tokens": db.n_draft, "target_rows": db.n_rows,
                    "gamma": [int(g) for g in db.gamma]},
         "emitted_tokens_per_s": round(emitted / (ms_step * 1e-3), 1),
-        "roofline": {"kernel": "gemm_bf16_skinny (all projections of a step)", "bound": "hbm",
+        "roofline": {"kernel": "gemm_bf16 (all projections of a step)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic() if args.workload == "cfg3" else None,
                      "bytes_per_launch": round(w_bytes / (gemm_launches / args.steps)),
                      "us_per_launch": round(gemm_us, 2), "us_per_launch_event_bracket": round(gemm_us_raw, 2),
                      "event_pair_overhead_us": round(pair_us, 2)},
         "stage_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in stages.items()},
     }
+    if args.workload == "rows1024":     # the projections are bound by the MFMA pipes at this row count
+        flops = w_bytes * db.n_rows     # 2 flops per weight and row, 2 bytes per weight
+        tflops = flops / (gemm_launches / args.steps) / (gemm_us * 1e-6) / 1e12
+        res["roofline"].update({"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4)})
     if args.layers:
         res["invalid"] = "debug run with fewer layers"
     if args.calibrate_copy:

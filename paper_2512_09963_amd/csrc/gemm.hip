@@ -150,18 +150,21 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
 }
 
 // More than 64 rows (a few hundred per step with tens of draft servers): the same streaming design
-// with a taller and wider wave tile.  A wave owns 32 output columns (two column tiles) and all
-// MT * 16 rows of its row chunk, so every activation fragment read from LDS feeds two MFMAs and every
-// weight fragment MT of them; a workgroup covers 128 columns.  Row chunks of one column block are
-// separate workgroups that read the same weights: workgroups are handed to the 8 XCDs round robin by
-// their linear index, so the chunks of a column block get indices that are 8 apart and land on the
-// same XCD one after the other, and all but the first find the weights in that XCD's L2.
-// grid (ceil(N/128 / 8) * 8 * m_chunks, S).
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_bf16_tall_kernel(const bf16_t* __restrict__ X,
-                                                             const bf16_t* __restrict__ Wp, float* __restrict__ P,
-                                                             int M, int N, int K, int k_per_split, int m_chunks) {
-  constexpr int NT = 2, DEPTH = 2;
+// with a taller and wider wave tile.  A wave owns NT column tiles and all MT * 16 rows of its row
+// chunk, so every activation fragment read from LDS feeds NT MFMAs and every weight fragment MT of
+// them; a workgroup covers NT * 64 columns.  Two shapes are used: (MT <= 10, NT = 2, two steps of
+// prefetch) while the weight stream still matters (up to a few hundred rows), and (MT = 8, NT = 4, no
+// register prefetch: the second wave on each SIMD hides the latency) for row counts where the MFMA
+// pipes are the bound.  Both fit two waves per SIMD.
+// Row chunks of one column block are separate workgroups that read the same weights: workgroups are
+// handed to the 8 XCDs round robin by their linear index, so the chunks of a column block get indices
+// that are 8 apart and land on the same XCD one after the other, and all but the first find the weights
+// in that XCD's L2.  grid (ceil(N / (64 NT) / 8) * 8 * m_chunks, S).
+template <int MT, int NT, int DEPTH>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __restrict__ X,
+                                                                const bf16_t* __restrict__ Wp,
+                                                                float* __restrict__ P, int M, int N, int K,
+                                                                int k_per_split, int m_chunks) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
@@ -335,6 +338,7 @@ struct GemmPlan {
   bool tall;      // gemm_bf16_tall_kernel (more than 64 rows, N a multiple of 128)
   int waves;      // skinny: waves per workgroup (4 or 8)
   int mt;         // row tiles per workgroup
+  int nt;         // tall: column tiles per wave (2 or 4)
   int m_chunks;   // row chunks (separate workgroups)
   int splits;     // K splits
   int k_per;      // k elements per split (multiple of 64)
@@ -344,9 +348,17 @@ static GemmPlan gemm_plan(int M, int N, int K) {
   GemmPlan p;
   const int tiles = ceil_div(M, 16);
   p.tall = tiles > 4 && N % 128 == 0;
+  p.nt = 1;
   int n_blocks;
-  if (p.tall) {
+  if (p.tall && tiles >= 40 && N % 256 == 0) {        // 640 rows and more: MFMA-bound shape
     p.waves = 4;
+    p.nt = 4;
+    p.mt = 8;
+    p.m_chunks = ceil_div(tiles, 8);
+    n_blocks = N / 256;
+  } else if (p.tall) {
+    p.waves = 4;
+    p.nt = 2;
     p.m_chunks = ceil_div(tiles, 10);
     const int per = ceil_div(tiles, p.m_chunks);      // 3 .. 10 row tiles per chunk
     p.mt = per <= 6 ? 6 : per <= 8 ? 8 : 10;
@@ -394,11 +406,15 @@ static void launch_skinny(const GemmPlan& p, const bf16_t* x, const bf16_t* w, f
 
 static void launch_tall(const GemmPlan& p, const bf16_t* x, const bf16_t* w, float* P, int M, int N, int K,
                         hipStream_t stream) {
-  const dim3 grid(ceil_div(N / 128, 8) * 8 * p.m_chunks, p.splits, 1);
+  const dim3 grid(ceil_div(N / (64 * p.nt), 8) * 8 * p.m_chunks, p.splits, 1);
+  if (p.nt == 4) {
+    gemm_bf16_tall_kernel<8, 4, 1><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
+    return;
+  }
   switch (p.mt) {
-    case 6: gemm_bf16_tall_kernel<6><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
-    case 8: gemm_bf16_tall_kernel<8><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
-    default: gemm_bf16_tall_kernel<10><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
+    case 6: gemm_bf16_tall_kernel<6, 2, 2><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
+    case 8: gemm_bf16_tall_kernel<8, 2, 2><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
+    default: gemm_bf16_tall_kernel<10, 2, 2><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
   }
 }
 

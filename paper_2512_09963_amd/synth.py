@@ -403,6 +403,13 @@ def config5(seed=MASTER_SEED, ms=LLAMA3_70B):
     return _verify_config("cfg5", ms, seed, gamma, np.full(16, 4096, np.int32), False, 0.0, 2.0)
 
 
+def config_rows1024(seed=MASTER_SEED, ms=LLAMA3_8B):
+    """Compute-bound row count for the projection kernels: 8 servers with blocks of 128 rows (the pending
+    token and 127 drafts) on an empty cache, i.e. 1024 target rows through the same verify call."""
+    gamma = np.full(8, 127, np.int32)
+    return _verify_config("rows1024", ms, seed, gamma, np.zeros(8, np.int32), False, 0.5, 1.0)
+
+
 def draft_tokens_of(cfg_tokens, gamma):
     """The draft tokens (without the pending tokens) in draft-row order."""
     cu = cu_rows_of(gamma)

@@ -156,6 +156,13 @@ def test_bf16_many_rows_use_the_tall_projection_kernel(n_servers, gmax):
     _run_case(ms, 81, gamma, ctx, 16, std=0.08)
 
 
+def test_bf16_block_of_hundreds_of_rows_on_an_empty_cache():
+    # 6 x 112 = 672 rows: the projection shape for row counts where the MFMA pipes are the bound, and
+    # attention with 28 query tiles per KV head (several passes of 8 waves) over keys of the block itself
+    ms = synth.ModelShape(1, 256, 4, 1, 128, 512, 1024, 500000.0, dtype="bf16")
+    _run_case(ms, 82, np.full(6, 111, np.int32), np.zeros(6, np.int32), 16, std=0.08)
+
+
 def test_bf16_page_size_48_not_a_power_of_two():
     ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
