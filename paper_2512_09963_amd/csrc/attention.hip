@@ -7,7 +7,7 @@
 //
 // bf16 path (MFMA): one workgroup per (server, KV head, KV split), one wave per 16 of the
 // T_i * G query rows that share the KV head (token-major, head-minor), so each K/V byte leaves
-// HBM once per workgroup; K/V stream through an LDS ring filled by direct global->LDS loads.
+// HBM once per workgroup; K/V stream through a two-stage LDS buffer filled by direct global->LDS loads.
 //   S^T = K Q^T : A operand = 16 keys x 32 channels, B operand = Q rows (kept in registers).
 //   The result layout puts a query row in lane%16 and 4 consecutive keys in each lane, which
 //   is already the A-operand layout of the second product, so P never leaves registers:

@@ -28,12 +28,8 @@
 namespace gs {
 namespace {
 
-#ifndef GS_GEMM_DEPTH
-#define GS_GEMM_DEPTH 4
-#endif
-#ifndef GS_GEMM_WGS
-#define GS_GEMM_WGS 512
-#endif
+constexpr int kSkinnyDepth = 4;     // k steps of weights and activations in flight per wave
+constexpr int kTargetWorkgroups = 512;   // about two per CU
 constexpr int kBK = 64;           // k elements per step
 constexpr int kLdsRow = kBK + 8;  // padded LDS row (bf16 elements): 144 bytes
 
@@ -374,7 +370,7 @@ static GemmPlan gemm_plan(int M, int N, int K) {
     n_blocks = N / (16 * p.waves);
   }
   const int wgs = n_blocks * p.m_chunks;
-  int want = (GS_GEMM_WGS + wgs / 2) / wgs;                // about two workgroups per CU
+  int want = (kTargetWorkgroups + wgs / 2) / wgs;                // about two workgroups per CU
   const int max_s = K / 512 > 0 ? K / 512 : 1;             // at least 8 steps per split
   int s = want < max_s ? want : max_s;
   if (s < 1) s = 1;
@@ -396,11 +392,11 @@ static void launch_skinny(const GemmPlan& p, const bf16_t* x, const bf16_t* w, f
   const int gx = p.m_chunks > 1 ? ceil_div(n_blocks, 8) * 8 * p.m_chunks : n_blocks;
   const dim3 grid(gx, p.splits, 1);
   switch (p.mt) {
-    case 1: gemm_bf16_skinny_kernel<1, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
-    case 2: gemm_bf16_skinny_kernel<2, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
-    case 4: gemm_bf16_skinny_kernel<4, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    case 1: gemm_bf16_skinny_kernel<1, kSkinnyDepth, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    case 2: gemm_bf16_skinny_kernel<2, kSkinnyDepth, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
+    case 4: gemm_bf16_skinny_kernel<4, kSkinnyDepth, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, 1); break;
     default:
-      gemm_bf16_skinny_kernel<8, GS_GEMM_DEPTH, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
+      gemm_bf16_skinny_kernel<8, kSkinnyDepth, NW><<<grid, 64 * NW, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
   }
 }
 
