@@ -187,6 +187,33 @@ def accept_inputs(seed, gamma, vocab, sigma, logit_scale=3.0, tag="accept"):
                         uniform01_f32(seed, (tag, "u_res", float_tag(sigma)), n))
 
 
+def loop_round_inputs(seed, round_idx, gamma, vocab, sigmas, logit_scale=3.0, tag="loop"):
+    """One round of the closed loop: like accept_inputs, but draft server i perturbs the target logits with
+    its own noise level sigmas[i] (heterogeneous acceptance rates), and every tensor is keyed by the round."""
+    gamma = np.asarray(gamma, dtype=np.int32)
+    sigmas = np.asarray(sigmas, dtype=np.float64)
+    n = gamma.size
+    cu_r = cu_rows_of(gamma)
+    cu_d = cu_draft_of(gamma)
+    R, G = int(cu_r[-1]), int(cu_d[-1])
+    key = (tag, int(round_idx))
+    tl = normal_f32(seed, key + ("target",), R * vocab, scale=logit_scale).reshape(R, vocab)
+    noise = normal_f32(seed, key + ("noise",), max(G, 1) * vocab).reshape(max(G, 1), vocab)
+    q = np.empty((G, vocab), dtype=np.float32)
+    for i in range(n):
+        for j in range(int(gamma[i])):
+            q[cu_d[i] + j] = draft_probs_from_logits(tl[cu_r[i] + j].astype(np.float64)
+                                                     + sigmas[i] * noise[cu_d[i] + j].astype(np.float64))
+    toks = sample_tokens(q, uniform01_f32(seed, key + ("u_tok",), G)) if G else np.zeros(0, np.int32)
+    return AcceptInputs(gamma, tl, q, toks, uniform01_f32(seed, key + ("u_acc",), G),
+                        uniform01_f32(seed, key + ("u_res",), n))
+
+
+def loop_policy_uniforms(seed, round_idx, count, tag="loop"):
+    """Uniforms in [0, 1) that the random allocation policy of a round consumes."""
+    return uniform01_f32(seed, (tag, int(round_idx), "policy"), count)
+
+
 def float_tag(x):
     return int(round(float(x) * 1000))
 
