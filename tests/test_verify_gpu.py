@@ -156,6 +156,17 @@ def test_bf16_many_rows_use_the_tall_projection_kernel(n_servers, gmax):
     _run_case(ms, 81, gamma, ctx, 16, std=0.08)
 
 
+def test_bf16_many_rows_with_widths_that_are_not_multiples_of_128():
+    # d = 192, the QKV width 192 and V = 960 are multiples of 64 only: these projections take the 64-column
+    # kernel with row chunks (column blocks padded to a multiple of 8 in the grid), gate/up the 128-column one
+    ms = synth.ModelShape(1, 192, 1, 1, 64, 320, 960, 10000.0, dtype="bf16")
+    rng = np.random.default_rng(83)
+    gamma = rng.integers(6, 13, 16).astype(np.int32)
+    ctx = rng.integers(0, 120, 16).astype(np.int32)
+    assert int(gamma.sum()) + 16 > 128
+    _run_case(ms, 83, gamma, ctx, 16, std=0.08)
+
+
 def test_bf16_block_of_hundreds_of_rows_on_an_empty_cache():
     # 6 x 112 = 672 rows: the projection shape for row counts where the MFMA pipes are the bound, and
     # attention with 28 query tiles per KV head (several passes of 8 waves) over keys of the block itself
