@@ -95,9 +95,7 @@ def run_steps(w, n_steps, sched):
     last = None
     for _ in range(n_steps):
         wl.verify(ver, kv, db, workspace=w["ws"], want_logits=False, out=w["out"])
-        for k in ("accepted_len", "accept_stat", "next_token"):
-            w["host"][k].copy_(w["out"][k], non_blocking=True)
-        torch.cuda.current_stream().synchronize()
+        torch.cuda.current_stream().synchronize()     # the 3N result scalars land in pinned host memory
         m = w["host"]["accepted_len"].numpy()
         st = w["host"]["accept_stat"].numpy()
         last = gsb.gs_schedule_gamma(m, st, db.gamma, sched["alpha"], sched["X"], sched["eta"], sched["beta"],
@@ -211,9 +209,12 @@ def main():
     db, ver = w["db"], w["ver"]
     dev = torch.device("cuda:0")
     w["ws"] = torch.empty(ver.gs_workspace_bytes(db.n_rows, db.n_servers, db.max_ctx), dtype=torch.uint8, device=dev)
-    w["out"] = gsb.make_accept_out(db.n_servers, db.n_draft, dev, want_ratio=False)
-    w["host"] = {k: torch.empty(db.n_servers, dtype=w["out"][k].dtype, pin_memory=True)
-                 for k in ("accepted_len", "accept_stat", "next_token")}
+    # the kernels store the 3N result scalars straight into pinned (device-mapped) host memory: the host
+    # scheduler reads them after the stream synchronisation, no copy is enqueued
+    w["host"] = {"accepted_len": torch.zeros(db.n_servers, dtype=torch.int32, pin_memory=True),
+                 "next_token": torch.zeros(db.n_servers, dtype=torch.int32, pin_memory=True),
+                 "accept_stat": torch.zeros(db.n_servers, dtype=torch.float32, pin_memory=True)}
+    w["out"] = dict(w["host"], ratio=None)
     sched = dict(alpha=np.full(db.n_servers, 0.5), X=np.ones(db.n_servers), eta=0.2, beta=0.5, C=int(db.n_draft))
 
     # timed region: K full steps, no instrumentation

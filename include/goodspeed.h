@@ -60,6 +60,9 @@ const char* gs_last_error(void);
 /* acceptance-rate update of Section III-C).                                    */
 /* ------------------------------------------------------------------------- */
 
+/* The output arrays are written by the kernels with plain stores: any memory the device can address
+ * will do, device memory or pinned host memory mapped into the device address space (then the results
+ * are on the host once the stream has been synchronised, without a copy). */
 typedef struct {
   int* accepted_len;   /* dev [N]  m_i in [0, gamma_i]: drafts kept before the first rejection      */
   int* next_token;     /* dev [N]  s'_i: drawn from normalised max(0, p_{m+1} - q_{m+1}) if          */

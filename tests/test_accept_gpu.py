@@ -9,7 +9,7 @@ from tests.parity import check_accept_outputs
 pytestmark = pytest.mark.gpu
 
 
-def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0):
+def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0, pinned_out=False):
     import torch
     from paper_2512_09963_amd import binding as gsb
     dev = torch.device("cuda:0")
@@ -31,6 +31,9 @@ def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0):
     ur = up(inp.u_resample, torch.float32)
     cu = torch.from_numpy(synth.cu_rows_of(inp.gamma)).to(dev)
     out = gsb.make_accept_out(n, G, dev, want_ratio)
+    if pinned_out:     # results stored by the kernels straight into device-mapped host memory
+        out = {k: (torch.empty(v.shape, dtype=v.dtype, pin_memory=True) if v is not None else None)
+               for k, v in out.items()}
     for k in ("accepted_len", "next_token"):
         out[k].fill_(-7)
     ws = torch.empty(gsb.gs_accept_workspace_bytes(n, R, V), dtype=torch.uint8, device=dev)
@@ -52,6 +55,12 @@ def test_small_ragged_batches(vocab, offset, sigma):
     got = _run_gpu(inp, offset_elems=offset)
     bands = _check(inp, got)
     assert bands["n_band_m"] + bands["n_band_tok"] <= 1
+
+
+def test_outputs_in_pinned_host_memory():
+    inp = synth.accept_inputs(synth.MASTER_SEED + 5, np.array([3, 0, 7, 2], np.int32), 1500, 1.0)
+    got = _run_gpu(inp, pinned_out=True)
+    check_accept_outputs(inp.gamma, inp.target_logits, inp.q_probs, inp.draft_tokens, inp.u_accept, inp.u_resample, got)
 
 
 def test_more_drafts_than_lanes_and_single_server():
