@@ -214,6 +214,11 @@ gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* ba
                           const gs_accept_out* out, float* logits_out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Test aid: with a non-NULL `trace` (dev, fp32 [(n_layers + 1)][R][d_model], caller-owned),
+ * every later gs_verify_batch on this ctx also copies the residual stream entering each decoder
+ * layer, and the final one that feeds the last norm, into it.  NULL switches it off. */
+gs_status gs_trace_residual(gs_ctx* ctx, float* trace);
+
 /* ------------------------------------------------------------------------- */
 /* Measurement aid (not part of the method): when enabled, gs_verify_batch      */
 /* brackets every stage with a pair of HIP events recorded on the caller's      */
@@ -221,11 +226,6 @@ gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* ba
 /* the summed milliseconds and the number of bracketed launches since the last  */
 /* read (arrays of GS_N_STAGES, host), and clears the record.                   */
 /* ------------------------------------------------------------------------- */
-/* Test aid: with a non-NULL `trace` (dev, fp32 [(n_layers + 1)][R][d_model], caller-owned),
- * every later gs_verify_batch on this ctx also copies the residual stream entering each decoder
- * layer, and the final one that feeds the last norm, into it.  NULL switches it off. */
-gs_status gs_trace_residual(gs_ctx* ctx, float* trace);
-
 enum { GS_STAGE_GEMM = 0, GS_STAGE_ATTENTION = 1, GS_STAGE_GLUE = 2, GS_STAGE_ACCEPT = 3, GS_N_STAGES = 4 };
 gs_status gs_profile_enable(gs_ctx* ctx, int on);
 gs_status gs_profile_read(gs_ctx* ctx, double* stage_ms, long* stage_launches);
