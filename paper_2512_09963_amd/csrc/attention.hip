@@ -5,17 +5,14 @@
 //   K pages [page][H_kv][slot][hd]   (key-major: a key's head vector is contiguous)
 //   V pages [page][H_kv][hd][slot]   (transposed: the slots of one channel are contiguous)
 //
-// bf16 path (MFMA): one workgroup per (server, KV head, KV split), one wave per 16 of the
+// bf16 path (MFMA): one workgroup per (server, KV head, KV split), one wave per 32 of the
 // T_i * G query rows that share the KV head (token-major, head-minor), so each K/V byte leaves
-// HBM once per workgroup; K/V stream through a two-stage LDS buffer filled by direct global->LDS loads.
-//   S^T = K Q^T : A operand = 16 keys x 32 channels, B operand = Q rows (kept in registers).
-//   The result layout puts a query row in lane%16 and 4 consecutive keys in each lane, which
-//   is already the A-operand layout of the second product, so P never leaves registers:
-//   O = P V     : B operand = V^T, 4 keys of one channel per lane, read from the verbatim copy
-//                 of the transposed V page.
-// The online-softmax state (running max, running sum) lives per query row in lane%16.  The
-// number of KV splits of a server follows its own context length (a fixed number of 32-key steps
-// per workgroup), so ragged batches stay balanced.  Partial results of the splits are merged by
+// HBM once per workgroup; K/V stream through a two-stage LDS buffer filled by direct global->LDS
+// loads.  The first product is computed transposed (S^T = K Q^T), which leaves a query's scores in
+// the registers of two lanes, in exactly the order the second product (O^T += V^T P) wants its P
+// operand, so P never leaves registers and neither product needs an LDS transpose.  The number of
+// KV splits of a server follows its own context length (a fixed number of 32-key steps per
+// workgroup), so ragged batches stay balanced.  Partial results of the splits are merged by
 // attn_combine_kernel.
 //
 // fp32 path: one wave per (row, head), lanes over keys, online softmax per lane.
@@ -27,6 +24,7 @@ namespace gs {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;
+
 
 __device__ __forceinline__ int server_of_row(const int* __restrict__ cu_rows, int n_servers, int r) {
   int lo = 0, hi = n_servers;
@@ -102,14 +100,23 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 // a two-stage LDS buffer with direct global->LDS loads (no register staging).  A stage has four
 // parts, K and V of either tile; part p is loaded by wave p % NW (waves 0..3 when NW > 4), whose
 // HD/32 load instructions of 1 KB each share one scalar base address.  One barrier per step both
-// publishes the stage that has landed and frees the stage that is refilled next.  K is placed in
-// LDS in MFMA-fragment order (lane l of fragment (tile, ks) finds its 16 bytes at fragment * 1 KB
-// + l * 16); V pages are copied verbatim ([channel][16 slots] per tile), which the second product
-// reads as 8-byte pieces without bank conflicts.
-// Wave w computes query tile w (16 of the T_i * G rows that share the KV head, token-major,
-// head-minor): S^T = K Q^T, online softmax per query row (lane%16), O += P V with P as a two-term
-// bf16 sum.  partial_o [R][H][max_splits][HD] fp32, partial_ml [R][H][max_splits][2]; splits
-// beyond a server's own count are never written and never read.
+// publishes the stage that has landed and frees the stage that is refilled next.  (Deeper buffers
+// were measured and are slower.)  K is placed in LDS so that lane (g, c) of fragment (tile, ks) holds
+// key c, channels 32 ks + 8 g .. at fragment * 1 KB + lane * 16; V pages are copied verbatim
+// ([channel][16 slots] per tile).
+// Wave w computes query rows 32 w .. 32 w + 31 of the T_i * G rows that share the KV head (token-major,
+// head-minor); both products use the 32x32x16 MFMA (twice the issue rate of the 16x16x32 one on this
+// chip):
+//   S^T (32 keys x 32 queries) = K Q^T : A = K, lane l holds key l%32 (tile l%32/16 of the step),
+//       channels 16 kk + 8 (l/32) .. of k step kk; B = Q^T, lane l holds query row l%32, same channels.
+//       Result register v of lane l is key 8 (v/4) + 4 (l/32) + v%4 of query l%32.
+//   O^T (hd x 32 queries) += V^T P : B = P straight from the result registers of the first product:
+//       k slot i of k step kk' (16 keys) is register 8 kk' + i, i.e. key 16 kk' + 8 (i/4) + 4 (l/32) + i%4;
+//       A = V^T in the same key order: channel 32 dt + l%32, two 8-byte runs of the transposed page.
+// A query row lives in lanes l and l + 32: one lane swap finishes its max and its sum, and the
+// accumulator rescale is a per-lane multiply.  P enters the second product as a two-term bf16 sum.
+// partial_o [R][H][max_splits][HD] fp32, partial_ml [R][H][max_splits][2]; splits beyond a server's own
+// count are never written and never read.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void wait_all_vector_loads() {
   // s_waitcnt vmcnt(0) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8;
@@ -117,98 +124,90 @@ __device__ __forceinline__ void wait_all_vector_loads() {
   __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));
 }
 
-// Reductions over the four 16-lane rows of a wave (lanes c, c+16, c+32, c+48), result in every lane.
-// The two swap instructions exchange rows between a register pair; fed the same value twice they
-// return (rows 0,0,2,2 | rows 1,1,3,3) and then (low half twice | high half twice).
-__device__ __forceinline__ float rows_max(float x) {
-  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+
+__device__ __forceinline__ float halves_max(float x) {
   auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-__device__ __forceinline__ float rows_sum(float x) {
-  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+__device__ __forceinline__ float halves_sum(float x) {
   auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 template <int HD, int G, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __restrict__ q,
-                                                            const bf16_t* __restrict__ k_pages,
-                                                            const bf16_t* __restrict__ v_pages,
-                                                            const int* __restrict__ block_table, int max_blocks,
-                                                            const int* __restrict__ cu_rows,
-                                                            const int* __restrict__ ctx_len, int page_size,
-                                                            int n_heads, int n_kv, int steps_per_split,
-                                                            int max_splits, int q_row_offset,
-                                                            float* __restrict__ partial_o,
-                                                            float* __restrict__ partial_ml) {
-  constexpr int KS = HD / 32;            // k steps of the first product = 1 KB loads per part
-  constexpr int DT = HD / 16;            // channel tiles of the second product
+__global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict__ q,
+                                                         const bf16_t* __restrict__ k_pages,
+                                                         const bf16_t* __restrict__ v_pages,
+                                                         const int* __restrict__ block_table, int max_blocks,
+                                                         const int* __restrict__ cu_rows,
+                                                         const int* __restrict__ ctx_len, int page_size,
+                                                         int n_heads, int n_kv, int steps_per_split,
+                                                         int max_splits, int q_row_offset,
+                                                         float* __restrict__ partial_o,
+                                                         float* __restrict__ partial_ml) {
+  constexpr int KS = HD / 32;            // 1 KB loads per part
+  constexpr int KK = HD / 16;            // k steps of the first product
+  constexpr int DT = HD / 32;            // 32-channel tiles of the second product
   constexpr int PART = HD * 32;          // bytes of K (or V) of one 16-key tile
   constexpr int STAGE = 4 * PART;        // K tile 0, K tile 1, V tile 0, V tile 1
   __shared__ __attribute__((aligned(16))) unsigned char ring[2 * STAGE];
 
   const int split = blockIdx.x, kh = blockIdx.y, srv = blockIdx.z;
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // provably uniform: scalar page lookups
-  const int g = lane >> 4, c = lane & 15;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int h = lane >> 5, c32 = lane & 31;
+  const int g = lane >> 4, c = lane & 15;            // loader roles (same as the 16-row kernel)
   const int row0 = cu_rows[srv];
   const int T = cu_rows[srv + 1] - row0;
   const int L = ctx_len[srv];
   const int n_keys = L + T;
   const int n_steps_all = (n_keys + 31) >> 5;
   const int step_begin = split * steps_per_split;
-  if (step_begin >= n_steps_all) return;                                // this server has fewer splits
-  const int n = min(steps_per_split, n_steps_all - step_begin);        // steps of this workgroup
+  if (step_begin >= n_steps_all) return;
+  const int n = min(steps_per_split, n_steps_all - step_begin);
   const int* bt = block_table + (size_t)srv * max_blocks;
   const bool page_pow2 = (page_size & (page_size - 1)) == 0;
   const int page_shift = 31 - __builtin_clz(page_size);
-  const int last_tile_key = ((n_keys - 1) >> 4) << 4;                   // first key of the last existing tile
+  const int last_tile_key = ((n_keys - 1) >> 4) << 4;
 
-  // ---- this wave's query tile
-  const int tile_row0 = q_row_offset + wave * 16;
-  const int rows = T * G - tile_row0;                                   // valid rows of the tile (<= 0: none)
+  // ---- this wave's 32 query rows
+  const int tile_row0 = q_row_offset + wave * 32;
+  const int rows = T * G - tile_row0;
   const bool has_rows = rows > 0;
-  const int my_lr = tile_row0 + c;
-  const bool my_ok = c < rows;
+  const int my_lr = tile_row0 + c32;
+  const bool my_ok = c32 < rows;
   const int my_j = my_ok ? my_lr / G : 0, my_hg = my_ok ? my_lr - my_j * G : 0;
-  const int limit = my_ok ? L + my_j : -1;                              // last key this lane's row may see
-  const int j_max = min(T - 1, (tile_row0 + 15) / G);
-  const int my_step_end = has_rows ? ((L + j_max) >> 5) + 1 : 0;       // causal: no key beyond L + j_max
+  const int limit = my_ok ? L + my_j : -1;
+  const int j_max = min(T - 1, (tile_row0 + 31) / G);
+  const int my_step_end = has_rows ? ((L + j_max) >> 5) + 1 : 0;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-  bf16x8_t qf[KS];
+  bf16x8_t qf[KK];
   {
-    const bf16_t* src = q + ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * HD + g * 8;
+    const bf16_t* src = q + ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * HD + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int kk = 0; kk < KK; ++kk) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (my_ok) v = *reinterpret_cast<const uint4*>(src + ks * 32);
-      qf[ks] = *reinterpret_cast<const bf16x8_t*>(&v);
+      if (my_ok) v = *reinterpret_cast<const uint4*>(src + kk * 16);
+      qf[kk] = *reinterpret_cast<const bf16x8_t*>(&v);
     }
   }
   float m_run = kNegBig, l_run = 0.f;
-  floatx4_t oacc[DT];
+  floatx16_t oacc[DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) oacc[dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
 
-  // ---- page-table lookup of the two 16-key tiles of a step (scalar loads; done one iteration before
-  // the stage is issued, so that no load instruction waits for it)
   auto lookup = [&](int step, int (&page)[2], int (&slot0)[2]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      const int key0 = min(step * 32 + t * 16, last_tile_key);   // a tile past the end re-reads the last one
-      // (page sizes are powers of two in practice: shifts instead of a scalar division sequence)
+      const int key0 = min(step * 32 + t * 16, last_tile_key);
       const int blk = page_pow2 ? key0 >> page_shift : key0 / page_size;
       page[t] = bt[blk];
       slot0[t] = key0 - blk * page_size;
     }
   };
-  // ---- stage loader.  Part p (0, 1: K of tile 0, 1; 2, 3: V of tile 0, 1) belongs to one wave; its
-  // address is a wave-uniform base (scalar registers) plus a per-lane byte offset that never changes:
-  //   K: lane (c, g) of fragment ks holds key slot0 + c, channels ks*32 + g*8 ..
-  //   V: 16-byte piece ch*64 + lane of the [HD][16 slots] tile is channel ch*32 + lane/2, half lane%2
   const unsigned k_lane_off = (unsigned)(c * HD + g * 8) * 2u;
   const unsigned v_lane_off = (unsigned)((lane >> 1) * page_size + (lane & 1) * 8) * 2u;
   const char* k_bytes = reinterpret_cast<const char*>(k_pages);
@@ -217,7 +216,7 @@ __global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __rest
     unsigned char* stage = ring + slot * STAGE;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      if (wave != (NW > 4 ? p : p % NW)) continue;           // uniform branch
+      if (wave != (NW > 4 ? p : p % NW)) continue;
       const int t = p & 1;
       const size_t head = (size_t)page[t] * n_kv + kh;
       if (p < 2) {
@@ -229,7 +228,7 @@ __global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __rest
                                            16, 0, 0);
       } else {
         const char* src = v_bytes + (head * HD * page_size + slot0[t]) * 2 + v_lane_off;
-        const size_t stride = (size_t)64 * page_size;        // 32 channels
+        const size_t stride = (size_t)64 * page_size;
 #pragma unroll
         for (int ch = 0; ch < KS; ++ch)
           __builtin_amdgcn_global_load_lds(src + ch * stride,
@@ -244,6 +243,11 @@ __global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __rest
   issue(0, pg_next, sl_next);
   if (1 < n) lookup(step_begin + 1, pg_next, sl_next);
 
+  // K fragment of k step kk for this lane: tile c32/16, fragment kk/2, lane group 2 (kk%2) + h, key c32%16
+  const int k_lane = ((c32 >> 4) * KS * 64 + h * 16 + (c32 & 15)) * 16;
+  // V: channel c32 of a 32-channel tile is 32 bytes per 16-key tile; this lane's runs start at slot 4h and 8 + 4h
+  const int v_lane = 2 * PART + c32 * 32 + h * 8;
+
   for (int s = 0; s < n; ++s) {
     const int step = step_begin + s;
     wait_all_vector_loads();     // this wave's parts of stage s have landed
@@ -255,131 +259,130 @@ __global__ __launch_bounds__(64 * NW) void attn_ring_kernel(const bf16_t* __rest
     if (step >= my_step_end) continue;
 
     const unsigned char* base = ring + (s & 1) * STAGE;
-    // first product S^T = K Q^T for the two 16-key tiles
-    bf16x8_t kf[2 * KS];
+    bf16x8_t kf[KK];
 #pragma unroll
-    for (int i = 0; i < 2 * KS; ++i) kf[i] = *reinterpret_cast<const bf16x8_t*>(base + i * 1024 + lane * 16);
-    floatx4_t sacc[2];
+    for (int kk = 0; kk < KK; ++kk)
+      kf[kk] = *reinterpret_cast<const bf16x8_t*>(base + k_lane + (kk >> 1) * 1024 + (kk & 1) * 512);
+    floatx16_t sacc;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      floatx4_t acc = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t * KS + ks], qf[ks], acc, 0, 0, 0);
-      sacc[t] = acc;
-    }
-    // online softmax: the query row is lane%16, its 32 keys are spread over the 4 lane groups
-    float p[8];
+    for (int kk = 0; kk < KK; ++kk) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc, 0, 0, 0);
+
+    float p[16];
     float corr;
     if (step * 32 + 31 <= L) {
-      // every key of the step is visible to every valid row: no masks
-      float mx = fmaxf(fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3])),
-                       fmaxf(fmaxf(sacc[1][0], sacc[1][1]), fmaxf(sacc[1][2], sacc[1][3])));
-      mx = rows_max(mx);
+      float mx = sacc[0];
+#pragma unroll
+      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[e]);
+      mx = halves_max(mx);
       const float m_new = fmaxf(m_run, mx * scale_log2);
       corr = __builtin_amdgcn_exp2f(m_run - m_new);
       float sum = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(fmaf(sacc[e >> 2][e & 3], scale_log2, -m_new));
+      for (int e = 0; e < 16; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(fmaf(sacc[e], scale_log2, -m_new));
         sum += p[e];
       }
-      l_run = l_run * corr + rows_sum(sum);
+      l_run = l_run * corr + halves_sum(sum);
       m_run = m_new;
     } else {
-      float sv[8];
+      float sv[16];
       float mx = kNegBig;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int key = step * 32 + (e >> 2) * 16 + g * 4 + (e & 3);
-        sv[e] = key <= limit ? sacc[e >> 2][e & 3] * scale_log2 : kNegBig;
+      for (int e = 0; e < 16; ++e) {
+        const int key = step * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+        sv[e] = key <= limit ? sacc[e] * scale_log2 : kNegBig;
         mx = fmaxf(mx, sv[e]);
       }
-      mx = rows_max(mx);
+      mx = halves_max(mx);
       const float m_new = fmaxf(m_run, mx);
       corr = __builtin_amdgcn_exp2f(m_run - m_new);
       float sum = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
+      for (int e = 0; e < 16; ++e) {
         p[e] = (sv[e] > kNegBig) ? __builtin_amdgcn_exp2f(sv[e] - m_new) : 0.f;
         sum += p[e];
       }
-      l_run = l_run * corr + rows_sum(sum);
+      l_run = l_run * corr + halves_sum(sum);
       m_run = m_new;
     }
-    // P enters the second product as a sum of two bf16 terms (value and rounding remainder), so
-    // the product sees 16 mantissa bits of P instead of 8
-    uint4 packed, packed_lo;
-    packed.x = pack_bf16x2(p[0], p[1]);
-    packed.y = pack_bf16x2(p[2], p[3]);
-    packed.z = pack_bf16x2(p[4], p[5]);
-    packed.w = pack_bf16x2(p[6], p[7]);
-    packed_lo.x = pack_bf16x2(p[0] - __uint_as_float(packed.x << 16), p[1] - __uint_as_float(packed.x & 0xffff0000u));
-    packed_lo.y = pack_bf16x2(p[2] - __uint_as_float(packed.y << 16), p[3] - __uint_as_float(packed.y & 0xffff0000u));
-    packed_lo.z = pack_bf16x2(p[4] - __uint_as_float(packed.z << 16), p[5] - __uint_as_float(packed.z & 0xffff0000u));
-    packed_lo.w = pack_bf16x2(p[6] - __uint_as_float(packed.w << 16), p[7] - __uint_as_float(packed.w & 0xffff0000u));
-    const bf16x8_t pf = *reinterpret_cast<const bf16x8_t*>(&packed);
-    const bf16x8_t pf_lo = *reinterpret_cast<const bf16x8_t*>(&packed_lo);
-    // the output accumulators hold query rows g*4 + i; their rescale factor sits in lane g*4 + i.
-    // Once the running maxima have settled every factor is exactly 1 and the rescale is skipped.
-    if (__any(corr != 1.0f)) {
-      float f[4];
+    // P as a two-term bf16 sum (value and rounding remainder); k step kk' takes registers 8 kk' .. 8 kk' + 7
+    bf16x8_t pf[2], pf_lo[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) f[i] = __shfl(corr, g * 4 + i);
+    for (int kk = 0; kk < 2; ++kk) {
+      uint4 hi, lo;
+      const float* pp = p + 8 * kk;
+      hi.x = pack_bf16x2(pp[0], pp[1]);
+      hi.y = pack_bf16x2(pp[2], pp[3]);
+      hi.z = pack_bf16x2(pp[4], pp[5]);
+      hi.w = pack_bf16x2(pp[6], pp[7]);
+      lo.x = pack_bf16x2(pp[0] - __uint_as_float(hi.x << 16), pp[1] - __uint_as_float(hi.x & 0xffff0000u));
+      lo.y = pack_bf16x2(pp[2] - __uint_as_float(hi.y << 16), pp[3] - __uint_as_float(hi.y & 0xffff0000u));
+      lo.z = pack_bf16x2(pp[4] - __uint_as_float(hi.z << 16), pp[5] - __uint_as_float(hi.z & 0xffff0000u));
+      lo.w = pack_bf16x2(pp[6] - __uint_as_float(hi.w << 16), pp[7] - __uint_as_float(hi.w & 0xffff0000u));
+      pf[kk] = *reinterpret_cast<const bf16x8_t*>(&hi);
+      pf_lo[kk] = *reinterpret_cast<const bf16x8_t*>(&lo);
+    }
+    // the rescale factor of a query row sits in the lanes that hold the row: a per-lane multiply,
+    // skipped once the running maxima have settled
+    if (__any(corr != 1.0f)) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) oacc[dt][i] *= f[i];
+        for (int e = 0; e < 16; ++e) oacc[dt][e] *= corr;
     }
-    // second product O += P V
-    const unsigned char* vb = base + 2 * PART + (c * 16 + g * 4) * 2;
-    uint2 v0[DT], v1[DT];
+    // second product
+    uint4 vv[DT][2];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      v0[dt] = *reinterpret_cast<const uint2*>(vb + dt * 512);
-      v1[dt] = *reinterpret_cast<const uint2*>(vb + PART + dt * 512);
-    }
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const unsigned char* vp = base + v_lane + kk * PART + dt * 1024;
+        const uint2 a = *reinterpret_cast<const uint2*>(vp);
+        const uint2 b = *reinterpret_cast<const uint2*>(vp + 16);
+        vv[dt][kk] = make_uint4(a.x, a.y, b.x, b.y);
+      }
     if (step * 32 + 32 > n_keys) {
-      // keys past the end of the sequence inside the last page hold stale data, so their V is
-      // zeroed (P is 0 there, but 0 * NaN would not be)
-      const int kb0 = step * 32 + g * 4, kb1 = kb0 + 16;
-      uint2 keep0, keep1;
-      keep0.x = (kb0 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 1 < n_keys ? 0xffff0000u : 0u);
-      keep0.y = (kb0 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 3 < n_keys ? 0xffff0000u : 0u);
-      keep1.x = (kb1 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 1 < n_keys ? 0xffff0000u : 0u);
-      keep1.y = (kb1 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 3 < n_keys ? 0xffff0000u : 0u);
+      // keys past the end of the sequence inside the last page hold stale data: zero their V
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        v0[dt].x &= keep0.x; v0[dt].y &= keep0.y;
-        v1[dt].x &= keep1.x; v1[dt].y &= keep1.y;
+      for (int kk = 0; kk < 2; ++kk) {
+        const int kb0 = step * 32 + 16 * kk + 4 * h, kb1 = kb0 + 8;
+        uint4 keep;
+        keep.x = (kb0 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 1 < n_keys ? 0xffff0000u : 0u);
+        keep.y = (kb0 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 3 < n_keys ? 0xffff0000u : 0u);
+        keep.z = (kb1 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 1 < n_keys ? 0xffff0000u : 0u);
+        keep.w = (kb1 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 3 < n_keys ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          vv[dt][kk].x &= keep.x; vv[dt][kk].y &= keep.y; vv[dt][kk].z &= keep.z; vv[dt][kk].w &= keep.w;
+        }
       }
     }
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const uint4 vv = make_uint4(v0[dt].x, v0[dt].y, v1[dt].x, v1[dt].y);
-      const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv);
-      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, vf, oacc[dt], 0, 0, 0);
-      oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_lo, vf, oacc[dt], 0, 0, 0);
-    }
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv[dt][kk]);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kk], oacc[dt], 0, 0, 0);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo[kk], oacc[dt], 0, 0, 0);
+      }
   }
 
-  // ---- this split's partial result for the tile's rows
-  if (!has_rows) return;
-  if (g == 0 && my_ok) {
-    const size_t idx = ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * max_splits + split;
-    partial_ml[idx * 2 + 0] = m_run;
-    partial_ml[idx * 2 + 1] = l_run;
+  // ---- this split's partial result: lane l holds query row l%32, channels 32 dt + 8 b + 4 h + (0..3)
+  if (!my_ok) return;
+  const size_t out_idx = ((size_t)(row0 + my_j) * n_heads + kh * G + my_hg) * max_splits + split;
+  if (h == 0) {
+    partial_ml[out_idx * 2 + 0] = m_run;
+    partial_ml[out_idx * 2 + 1] = l_run;
   }
+  float* dst = partial_o + out_idx * HD + 4 * h;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int lrow = g * 4 + i;
-    if (lrow < rows) {
-      const int lr = tile_row0 + lrow;
-      const int j = lr / G, hg = lr - j * G;
-      float* dst = partial_o + (((size_t)(row0 + j) * n_heads + kh * G + hg) * max_splits + split) * HD;
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) dst[dt * 16 + c] = oacc[dt][i];
-    }
-  }
+    for (int b = 0; b < 4; ++b)
+      *reinterpret_cast<float4*>(dst + dt * 32 + b * 8) =
+          make_float4(oacc[dt][4 * b], oacc[dt][4 * b + 1], oacc[dt][4 * b + 2], oacc[dt][4 * b + 3]);
 }
 
 // attn_out[r][h*HD + d] = sum_s o_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M) over the row's server's own
@@ -415,9 +418,10 @@ __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const f
 // while a floor on the steps per workgroup bounds what the partial results cost.
 void attention_plan(int n_kv, int group, int max_block_tokens, long total_steps, int max_steps, int* steps_per_split,
                     int* max_splits) {
-  const int tiles = ceil_div(max_block_tokens * group, 16);
+  const int tiles = ceil_div(max_block_tokens * group, 32);
   const int waves = tiles < 8 ? (tiles > 0 ? tiles : 1) : 8;
-  const int wgs_per_cu = 16 / waves < 5 ? 16 / waves : 5;      // 16 waves by registers, 5 workgroups by LDS
+  constexpr int kWavesPerCu = 8;     // by registers
+  const int wgs_per_cu = kWavesPerCu / waves < 5 ? (kWavesPerCu / waves > 0 ? kWavesPerCu / waves : 1) : 5;   // 5 workgroups by LDS
   const long slots = 256L * wgs_per_cu;
   long sps = (total_steps * n_kv + 4 * slots - 1) / (4 * slots);
   if (sps < 6) sps = 6;
@@ -425,7 +429,10 @@ void attention_plan(int n_kv, int group, int max_block_tokens, long total_steps,
   if (sps < lo) sps = lo;
   if (sps > max_steps) sps = max_steps > 0 ? max_steps : 1;
   *steps_per_split = (int)sps;
-  *max_splits = (int)((max_steps + sps - 1) / sps);
+  // the split count is also the stride (in 512-byte partial rows) between the partial results of
+  // neighbouring (row, head) pairs: kept odd, because a power-of-two stride sends all partial stores of a
+  // workgroup to the same few memory channels (measured: 110 instead of 81 us per layer at a stride of 32)
+  *max_splits = (int)((max_steps + sps - 1) / sps) | 1;
 }
 
 size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits) {
@@ -437,14 +444,14 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
                                int max_blocks, const int* cu_rows, const int* ctx_len, int n_servers, int page_size,
                                int n_heads, int n_kv, int max_block_tokens, int steps_per_split, int max_splits,
                                float* po, float* pml, hipStream_t stream) {
-  const int tiles = ceil_div(max_block_tokens * G, 16);
+  const int tiles = ceil_div(max_block_tokens * G, 32);
   dim3 grid(max_splits, n_kv, n_servers);
   for (int t0 = 0; t0 < tiles; t0 += 8) {      // at most 8 query tiles (waves) per workgroup
     const int waves = tiles - t0 < 8 ? tiles - t0 : 8;
 #define GS_RING(NW_)                                                                                              \
-  attn_ring_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks,    \
-                                                                 cu_rows, ctx_len, page_size, n_heads, n_kv,      \
-                                                                 steps_per_split, max_splits, t0 * 16, po, pml)
+  attn_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,   \
+                                                         ctx_len, page_size, n_heads, n_kv, steps_per_split,      \
+                                                         max_splits, t0 * 32, po, pml)
     switch (waves) {
       case 1: GS_RING(1); break;
       case 2: GS_RING(2); break;
@@ -456,7 +463,7 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
       default: GS_RING(8); break;
     }
 #undef GS_RING
-    GS_LAUNCH_CHECK("attn_ring");
+    GS_LAUNCH_CHECK("attn");
   }
   return GS_OK;
 }

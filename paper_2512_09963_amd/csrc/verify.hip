@@ -102,7 +102,7 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   p.act = c.take<char>(R * m.d_ffn * ctx->elem);
   // the planner never uses more than 32 splits per server and never fewer than 6 steps per split
   const int max_steps = (max_ctx + 31) / 32;
-  const int max_splits = std::max(1, std::min(32, (max_steps + 5) / 6));
+  const int max_splits = std::max(1, std::min(32, (max_steps + 5) / 6)) | 1;   // odd, like the planner's
   (void)max_servers;
   p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
   p.logits = c.take<float>(R * m.vocab);
