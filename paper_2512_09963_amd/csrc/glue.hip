@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ embed,
 
 // x[r] += sum_s partial[s][r] (if partial), then h[r] = x[r] * w / sqrt(mean(x[r]^2) + eps).
 // One workgroup per row, one float4 per lane and pass; the loads of the S partials are
-// independent, so they are issued back to back (d % 4 == 0).
+// independent, so they are issued back to back (d % 4 == 0).  The first two passes of a row (all of it for
+// d <= 8192 at 1024 lanes) stay in registers between the sum of squares and the scaling, and the norm
+// weights are fetched before the reduction, so the second phase touches no memory but its stores.
 template <typename T>
 __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ partial,
                                                            int n_splits, int n_rows, const float* __restrict__ w,
@@ -51,8 +53,9 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x
   const int d4 = d >> 2;
   const size_t split_stride = (size_t)n_rows * d4;
   const float4* pr = reinterpret_cast<const float4*>(partial) + (size_t)r * d4;
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < d4; i += blockDim.x) {
+  const float4* wr = reinterpret_cast<const float4*>(w);
+  // element i of the row with the partial sums added (and stored back to the residual stream)
+  auto fetch = [&](int i) {
     float4 v = xr[i];
     if (partial) {
       float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0;
@@ -70,19 +73,38 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x
       v.x += a0.x + a1.x; v.y += a0.y + a1.y; v.z += a0.z + a1.z; v.w += a0.w + a1.w;
       xr[i] = v;
     }
-    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-  }
-  const float tot = block_sum(ss, sh);
-  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  const float4* wr = reinterpret_cast<const float4*>(w);
-  for (int i = threadIdx.x; i < d4; i += blockDim.x) {
-    const float4 v = xr[i], ww = wr[i];
+    return v;
+  };
+  auto squares = [](const float4& v) { return (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w); };
+  auto emit = [&](int i, const float4& v, const float4& ww, float inv) {
     T* dst = h + (size_t)r * d + 4 * i;
     Storage<T>::store(dst + 0, v.x * inv * ww.x);
     Storage<T>::store(dst + 1, v.y * inv * ww.y);
     Storage<T>::store(dst + 2, v.z * inv * ww.z);
     Storage<T>::store(dst + 3, v.w * inv * ww.w);
+  };
+  const int bd = blockDim.x;
+  const int i0 = threadIdx.x, i1 = threadIdx.x + bd;
+  const bool has0 = i0 < d4, has1 = i1 < d4;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 v0 = zero, v1 = zero, w0 = zero, w1 = zero;
+  float ss = 0.f;
+  if (has0) {
+    w0 = wr[i0];
+    v0 = fetch(i0);
+    ss += squares(v0);
   }
+  if (has1) {
+    w1 = wr[i1];
+    v1 = fetch(i1);
+    ss += squares(v1);
+  }
+  for (int i = i1 + bd; i < d4; i += bd) ss += squares(fetch(i));     // rows wider than two passes
+  const float tot = block_sum(ss, sh);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  if (has0) emit(i0, v0, w0, inv);
+  if (has1) emit(i1, v1, w1, inv);
+  for (int i = i1 + bd; i < d4; i += bd) emit(i, xr[i], wr[i], inv);
 }
 
 // Per-row facts that every layer of a step shares: where the row's K/V go (page, slot) and the
