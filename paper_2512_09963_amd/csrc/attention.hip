@@ -389,22 +389,25 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict_
 // splits.  grid (R*H), block HD.
 template <int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const float* __restrict__ partial_ml,
-                                    int max_splits, int steps_per_split, const int* __restrict__ cu_rows,
-                                    const int* __restrict__ ctx_len, int n_servers, int n_heads,
-                                    bf16_t* __restrict__ attn_out) {
+                                    int max_splits, int steps_per_split, const int4* __restrict__ row_info,
+                                    int n_heads, bf16_t* __restrict__ attn_out) {
   const size_t rh = blockIdx.x;
   const int d = threadIdx.x;
-  const int r = (int)(rh / n_heads);
-  const int srv = server_of_row(cu_rows, n_servers, r);
-  const int n_keys = ctx_len[srv] + (cu_rows[srv + 1] - cu_rows[srv]);
+  const int n_keys = row_info[rh / n_heads].z;      // keys of the row's server (per-row table of the step)
   const int n_splits = (((n_keys + 31) >> 5) + steps_per_split - 1) / steps_per_split;
-  float M = kNegBig;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, partial_ml[(rh * max_splits + s) * 2]);
-  float Lsum = 0.f, acc = 0.f;
+  // one pass with a running maximum, so that no load waits for the maximum over all splits
+  const float2* ml = reinterpret_cast<const float2*>(partial_ml) + rh * max_splits;
+  const float* po = partial_o + rh * max_splits * HD + d;
+  float M = kNegBig, Lsum = 0.f, acc = 0.f;
+#pragma unroll 4
   for (int s = 0; s < n_splits; ++s) {
-    const float f = exp2f(partial_ml[(rh * max_splits + s) * 2] - M);
-    Lsum += partial_ml[(rh * max_splits + s) * 2 + 1] * f;
-    acc += partial_o[(rh * max_splits + s) * HD + d] * f;
+    const float2 st = ml[s];
+    const float o = po[(size_t)s * HD];
+    const float Mn = fmaxf(M, st.x);
+    const float c = exp2f(M - Mn), f = exp2f(st.x - Mn);
+    Lsum = Lsum * c + st.y * f;
+    acc = acc * c + o * f;
+    M = Mn;
   }
   attn_out[rh * HD + d] = float_to_bf16(acc / Lsum);
 }
@@ -472,8 +475,8 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
-                           int max_block_tokens, int steps_per_split, int max_splits, float* scratch, void* attn_out,
-                           hipStream_t stream) {
+                           int max_block_tokens, int steps_per_split, int max_splits, const void* row_info,
+                           float* scratch, void* attn_out, hipStream_t stream) {
   if (dtype == GS_F32) {
     dim3 grid(n_rows, n_heads);
     const float* qf = static_cast<const float*>(q);
@@ -505,12 +508,12 @@ gs_status launch_attention(int dtype, const void* q, const void* k_pages, const 
 #undef GS_ATTN_CASE
   if (st != GS_OK) return st;
   if (hd == 128)
-    attn_combine_kernel<128><<<n_rows * n_heads, 128, 0, stream>>>(po, pml, max_splits, steps_per_split, cu_rows,
-                                                                   ctx_len, n_servers, n_heads,
+    attn_combine_kernel<128><<<n_rows * n_heads, 128, 0, stream>>>(po, pml, max_splits, steps_per_split,
+                                                                   static_cast<const int4*>(row_info), n_heads,
                                                                    static_cast<bf16_t*>(attn_out));
   else
-    attn_combine_kernel<64><<<n_rows * n_heads, 64, 0, stream>>>(po, pml, max_splits, steps_per_split, cu_rows,
-                                                                 ctx_len, n_servers, n_heads,
+    attn_combine_kernel<64><<<n_rows * n_heads, 64, 0, stream>>>(po, pml, max_splits, steps_per_split,
+                                                                 static_cast<const int4*>(row_info), n_heads,
                                                                  static_cast<bf16_t*>(attn_out));
   GS_LAUNCH_CHECK("attn_combine");
   return GS_OK;

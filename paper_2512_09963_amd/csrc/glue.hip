@@ -107,17 +107,19 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float* __restrict__ x
   for (int i = i1 + bd; i < d4; i += bd) emit(i, xr[i], wr[i], inv);
 }
 
-// Per-row facts that every layer of a step shares: where the row's K/V go (page, slot) and the
-// rotary sine/cosine of its position.  rope [R][hd/2] (cos, sin).  The angle pos * theta^(-2i/hd)
+// Per-row facts that every layer of a step shares: where the row's K/V go (page, slot), how many keys
+// its server has after the append, and the rotary sine/cosine of its position.  rope [R][hd/2] (cos, sin).  The angle pos * theta^(-2i/hd)
 // reaches thousands of radians: it is formed in double, so that the rotated values agree with a
 // float64 evaluation to fp32 rounding.  grid R, block hd/2.
 __global__ void row_meta_kernel(const int* __restrict__ cu_rows, const int* __restrict__ ctx_len, int n_servers,
                                 const int* __restrict__ block_table, int max_blocks, int page_size, int hd,
-                                double log2_theta, int2* __restrict__ row_slot, float2* __restrict__ rope) {
+                                double log2_theta, int4* __restrict__ row_slot, float2* __restrict__ rope) {
   const int r = blockIdx.x, i = threadIdx.x;
   const int srv = server_of_row(cu_rows, n_servers, r);
   const int pos = ctx_len[srv] + (r - cu_rows[srv]);
-  if (i == 0) row_slot[r] = make_int2(block_table[(size_t)srv * max_blocks + pos / page_size], pos % page_size);
+  if (i == 0)      // (page, slot) of the row's own K/V, keys of its server after the append, server
+    row_slot[r] = make_int4(block_table[(size_t)srv * max_blocks + pos / page_size], pos % page_size,
+                            ctx_len[srv] + (cu_rows[srv + 1] - cu_rows[srv]), srv);
   const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
   double sn, cs;
   sincos((double)pos * inv_freq, &sn, &cs);
@@ -129,7 +131,7 @@ __global__ void row_meta_kernel(const int* __restrict__ cu_rows, const int* __re
 // grid (R, (H + 2 H_kv) * hd/2 / 256): a thread owns the element pair (i, i + hd/2) of one head.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, int n_rows,
-                                                          const int2* __restrict__ row_slot,
+                                                          const int4* __restrict__ row_slot,
                                                           const float2* __restrict__ rope, int page_size,
                                                           int n_heads, int n_kv, int hd, T* __restrict__ q_out,
                                                           T* __restrict__ k_pages, T* __restrict__ v_pages) {
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
     a += src[(size_t)s * split_stride];
     b += src[(size_t)s * split_stride + half];
   }
-  const int2 ps = row_slot[r];
+  const int4 ps = row_slot[r];
   if (head < n_heads + n_kv) {
     const float2 cs = rope[(size_t)r * half + i];
     const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
@@ -162,19 +164,31 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
 }
 
 // act[r][f] = silu(gate) * up with gate = sum_s gu[s][r][f], up = sum_s gu[s][r][F + f].
-template <typename T>
+// VEC: four features per lane (F % 4 == 0).
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int n_splits, int n_rows, int F,
                                                      T* __restrict__ act) {
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  constexpr int W = VEC ? 4 : 1;
+  const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * W;
   if (idx >= (size_t)n_rows * F) return;
   const int r = (int)(idx / F), f = (int)(idx - (size_t)r * F);
-  float gt = 0.f, up = 0.f;
+  float gt[W], up[W];
+#pragma unroll
+  for (int k = 0; k < W; ++k) gt[k] = up[k] = 0.f;
   for (int s = 0; s < n_splits; ++s) {
     const float* row = gu + ((size_t)s * n_rows + r) * 2 * F;
-    gt += row[f];
-    up += row[F + f];
+    if constexpr (VEC) {
+      const float4 g4 = *reinterpret_cast<const float4*>(row + f);
+      const float4 u4 = *reinterpret_cast<const float4*>(row + F + f);
+      gt[0] += g4.x; gt[1] += g4.y; gt[2] += g4.z; gt[3] += g4.w;
+      up[0] += u4.x; up[1] += u4.y; up[2] += u4.z; up[3] += u4.w;
+    } else {
+      gt[0] += row[f];
+      up[0] += row[F + f];
+    }
   }
-  Storage<T>::store(act + idx, gt / (1.0f + expf(-gt)) * up);
+#pragma unroll
+  for (int k = 0; k < W; ++k) Storage<T>::store(act + idx + k, gt[k] / (1.0f + expf(-gt[k])) * up[k]);
 }
 
 }  // namespace
@@ -209,7 +223,7 @@ gs_status launch_row_meta(const int* cu_rows, const int* ctx_len, int n_servers,
                           int max_blocks, int page_size, int hd, float rope_theta, void* row_slot, void* rope,
                           hipStream_t stream) {
   row_meta_kernel<<<n_rows, hd / 2, 0, stream>>>(cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size, hd,
-                                                 log2((double)rope_theta), static_cast<int2*>(row_slot),
+                                                 log2((double)rope_theta), static_cast<int4*>(row_slot),
                                                  static_cast<float2*>(rope));
   GS_LAUNCH_CHECK("row_meta");
   return GS_OK;
@@ -220,7 +234,7 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              void* k_pages, void* v_pages, hipStream_t stream) {
   const dim3 grid(n_rows, ceil_div((n_heads + 2 * n_kv) * (hd / 2), 256));
   GS_DISPATCH_T(dtype, rope_append_kernel<T><<<grid, 256, 0, stream>>>(
-                           qkv, n_splits, n_rows, static_cast<const int2*>(row_slot),
+                           qkv, n_splits, n_rows, static_cast<const int4*>(row_slot),
                            static_cast<const float2*>(rope), page_size, n_heads, n_kv, hd, static_cast<T*>(q_out),
                            static_cast<T*>(k_pages), static_cast<T*>(v_pages));)
   GS_LAUNCH_CHECK("rope_append");
@@ -229,8 +243,13 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
 
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream) {
   const size_t total = (size_t)n_rows * F;
-  const int blocks = (int)((total + 255) / 256);
-  GS_DISPATCH_T(dtype, swiglu_kernel<T><<<blocks, 256, 0, stream>>>(gu, n_splits, n_rows, F, static_cast<T*>(act));)
+  if (F % 4 == 0) {
+    const int blocks = (int)((total / 4 + 255) / 256);
+    GS_DISPATCH_T(dtype, swiglu_kernel<T, true><<<blocks, 256, 0, stream>>>(gu, n_splits, n_rows, F, static_cast<T*>(act));)
+  } else {
+    const int blocks = (int)((total + 255) / 256);
+    GS_DISPATCH_T(dtype, swiglu_kernel<T, false><<<blocks, 256, 0, stream>>>(gu, n_splits, n_rows, F, static_cast<T*>(act));)
+  }
   GS_LAUNCH_CHECK("swiglu");
   return GS_OK;
 }

@@ -29,7 +29,8 @@ size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_split
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
-                           int max_block_tokens, int steps_per_split, int max_splits, float* scratch, void* attn_out,
+                           int max_block_tokens, int steps_per_split, int max_splits, const void* row_info,
+                           float* scratch, void* attn_out,
                            hipStream_t stream);
 gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
                         const float* q_probs, const int* draft_tokens, const float* u_accept,
@@ -66,7 +67,7 @@ struct Plan {
   float* attn_scratch;
   float* logits;
   int* draft_tokens;
-  void* row_slot;   // [R] (page, slot) of the row's own K/V
+  void* row_slot;   // [R] (page, slot of the row's own K/V, keys of its server, server)
   void* rope;       // [R][hd/2] (cos, sin)
   void* accept_ws;
   size_t bytes;
@@ -107,7 +108,7 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
   p.logits = c.take<float>(R * m.vocab);
   p.draft_tokens = c.take<int>(R);
-  p.row_slot = c.take<int>(2 * R);
+  p.row_slot = c.take<int>(4 * R);
   p.rope = c.take<float>(R * m.head_dim);
   size_t acc = 0;
   for (int n = 1; n <= max_servers; ++n) acc = std::max(acc, gs::accept_workspace_bytes(n, max_rows, m.vocab));
@@ -345,7 +346,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
                                   p.rope, kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, p.q, kl, vl, stream));
     GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
                                 kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_sps, attn_splits,
-                                p.attn_scratch, p.attn, stream));
+                                p.row_slot, p.attn_scratch, p.attn, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
     GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
                                                    ctx->norm2[l], m.rms_eps, p.h, d, stream));
