@@ -186,6 +186,8 @@ typedef struct {
   const float* u_resample;   /* dev  [N]                                                       */
 } gs_batch;
 
+/* A gs_ctx holds the model description, the weight pointers and small host-side planning tables.
+ * Calls on one context must not overlap in time (use one context per calling thread). */
 typedef struct gs_ctx gs_ctx;
 
 /* Validates the shape and copies the descriptor and the per-layer pointer tables.

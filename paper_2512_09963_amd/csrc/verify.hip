@@ -53,6 +53,9 @@ struct gs_ctx {
   std::vector<hipEvent_t> ev_start, ev_stop;
   std::vector<int> ev_stage;
   size_t ev_used = 0;
+  // workspace planning: prefix maxima of the split-K partial sizes over the row count (filled on demand;
+  // a context is used by one thread at a time)
+  mutable std::vector<size_t> partial_prefix_max;
 };
 
 namespace {
@@ -73,20 +76,25 @@ struct Plan {
   size_t bytes;
 };
 
-size_t max_partial_floats(const gs_model_desc& m, int max_rows) {
+// Largest split-K partial buffer any projection needs for up to max_rows rows.  The split counts are not
+// monotone in the row count, so the maximum runs over every row count; the prefix maxima are kept in the
+// context (one entry per row count seen so far), which makes the per-call cost a table lookup.
+size_t max_partial_floats(const gs_ctx* ctx, int max_rows) {
+  const gs_model_desc& m = ctx->desc;
   const int qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
   const int hq = m.n_heads * m.head_dim;
-  size_t best = 0;
-  for (int M = 1; M <= max_rows; ++M) {
+  std::vector<size_t>& best = ctx->partial_prefix_max;
+  if (best.empty()) best.push_back(0);
+  for (int M = (int)best.size(); M <= max_rows; ++M) {
     size_t a = (size_t)gs::gemm_splits(m.dtype, M, qkv, m.d_model) * M * qkv;
     size_t b = (size_t)gs::gemm_splits(m.dtype, M, m.d_model, hq) * M * m.d_model;
     size_t c = (size_t)gs::gemm_splits(m.dtype, M, 2 * m.d_ffn, m.d_model) * M * 2 * m.d_ffn;
     size_t d = (size_t)gs::gemm_splits(m.dtype, M, m.d_model, m.d_ffn) * M * m.d_model;
     const int sv = gs::gemm_splits(m.dtype, M, m.vocab, m.d_model);
     size_t e = sv > 1 ? (size_t)sv * M * m.vocab : 0;   // LM head partials only when it is split
-    best = std::max(std::max(best, a), std::max(std::max(b, e), std::max(c, d)));
+    best.push_back(std::max(std::max(best.back(), a), std::max(std::max(b, e), std::max(c, d))));
   }
-  return best;
+  return best[max_rows];
 }
 
 Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, void* ws) {
@@ -97,7 +105,7 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   Plan p;
   p.x = c.take<float>(R * m.d_model);
   p.h = c.take<char>(R * m.d_model * ctx->elem);
-  p.partial = c.take<float>(max_partial_floats(m, max_rows));
+  p.partial = c.take<float>(max_partial_floats(ctx, max_rows));
   p.q = c.take<char>(R * hq * ctx->elem);
   p.attn = c.take<char>(R * hq * ctx->elem);
   p.act = c.take<char>(R * m.d_ffn * ctx->elem);
@@ -304,10 +312,9 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
       return gs::fail(GS_EINVAL, "accept outputs are required when q_probs is given");
     if (!b->u_resample || (G > 0 && !b->u_accept)) return gs::fail(GS_EINVAL, "uniforms are required");
   }
-  const size_t need_ws = make_plan(ctx, (int)R, n, max_ctx, nullptr).bytes;
-  if (workspace_bytes < need_ws)
-    return gs::fail(GS_ECAPACITY, "workspace of %zu bytes, this batch needs %zu", workspace_bytes, need_ws);
-  const Plan p = make_plan(ctx, (int)R, n, max_ctx, workspace);
+  const Plan p = make_plan(ctx, (int)R, n, max_ctx, workspace);      // carves addresses only
+  if (workspace_bytes < p.bytes)
+    return gs::fail(GS_ECAPACITY, "workspace of %zu bytes, this batch needs %zu", workspace_bytes, p.bytes);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const int rows = (int)R, d = m.d_model, hq = m.n_heads * m.head_dim, qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
   const int F = m.d_ffn;
