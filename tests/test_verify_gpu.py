@@ -174,6 +174,21 @@ def test_bf16_block_of_hundreds_of_rows_on_an_empty_cache():
     _run_case(ms, 82, np.full(6, 111, np.int32), np.zeros(6, np.int32), 16, std=0.08)
 
 
+@pytest.mark.parametrize("group,gamma,ctx", [
+    # rows per KV head T*G around the 32-row wave tile; keys around the 32-key step and the 16-key page
+    (4, [7, 8, 15, 16], [0, 1, 15, 16]),
+    (4, [7, 8, 15, 16], [17, 24, 31, 32]),
+    (8, [3, 4, 7, 8], [33, 63, 64, 65]),
+    (1, [31, 32, 63, 0], [95, 96, 97, 191]),
+    # contexts around multiples of the steps-per-workgroup choices (6 steps = 192 keys, and larger)
+    (4, [2, 2, 2, 2, 2, 2], [190, 191, 192, 193, 383, 385]),
+    (2, [5, 1, 9, 3], [1023, 1024, 2047, 2049]),
+])
+def test_bf16_attention_tile_and_split_boundaries(group, gamma, ctx):
+    ms = synth.ModelShape(1, 128, 2 * group, 2, 64, 128, 512, 10000.0, dtype="bf16")
+    _run_case(ms, 84, np.array(gamma, np.int32), np.array(ctx, np.int32), 16, std=0.08)
+
+
 def test_bf16_page_size_48_not_a_power_of_two():
     ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
