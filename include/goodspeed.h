@@ -50,7 +50,7 @@ typedef enum {
   GS_EUNSUPPORTED = -5
 } gs_status;
 
-enum { GS_F32 = 0, GS_BF16 = 1 };
+enum { GS_F32 = 0, GS_BF16 = 1, GS_W4 = 2 /* bf16 activations, KV and embedding; 4-bit projection weights */ };
 
 /* Message of the last error on this thread (static storage, never NULL). */
 const char* gs_last_error(void);
@@ -131,7 +131,8 @@ gs_status gs_schedule_gamma(int n, const int* accepted_len, const float* accept_
 typedef struct {
   int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rope_theta, rms_eps;
-  int dtype;            /* GS_F32 or GS_BF16: storage type of weights, KV pages and GEMM operands */
+  int dtype;            /* GS_F32 or GS_BF16: storage type of weights, KV pages and GEMM operands;  */
+                        /* GS_W4: as GS_BF16, but the projection matrices are 4-bit (see below)   */
 } gs_model_desc;
 
 /*
@@ -146,6 +147,23 @@ typedef struct {
  */
 gs_status gs_pack_weight(const void* w_rowmajor /* dev */, void* w_packed /* dev, same size, not in place */,
                          int n_out, int k_in, int dtype, void* hip_stream);
+
+/*
+ * 4-bit projection weights for GS_W4 models (weight-only quantisation in groups of 128 inputs, the format
+ * family of the AWQ checkpoints of the paper's 70B verifier, Section IV-A):
+ *   W[n][k] = (code[n][k] - zero[n][k/128]) * scale[n][k/128],  codes and zeros in 0..15, scales bf16;
+ * every dequantised weight is rounded to bf16 (nearest even) before it enters the product.
+ * gs_pack_weight_w4 turns the three arrays into the layout the projection kernel streams
+ * (gs_w4_packed_bytes bytes: the codes tile-packed like the bf16 weights, then one word of scale and zero
+ * per column and group).  k_in must be a multiple of 128, n_out of 64.
+ *   codes   dev uint8 [n_out][k_in]      one code per byte
+ *   scales  dev bf16  [n_out][k_in/128]
+ *   zeros   dev uint8 [n_out][k_in/128]
+ * Errors: GS_EINVAL, GS_ESHAPE, GS_EDEVICE.
+ */
+size_t gs_w4_packed_bytes(int n_out, int k_in);
+gs_status gs_pack_weight_w4(const uint8_t* codes, const void* scales, const uint8_t* zeros, void* w_packed,
+                            int n_out, int k_in, void* hip_stream);
 
 typedef struct {
   const void* embed;          /* dev [V, d] row-major                                    */

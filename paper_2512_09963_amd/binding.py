@@ -17,11 +17,13 @@ import torch  # imported before the library so that both share one HIP runtime
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("GS_LIB_PATH") or os.path.join(_HERE, "libgoodspeed.so")   # override: development builds
 
-GS_F32, GS_BF16 = 0, 1
+GS_F32, GS_BF16, GS_W4 = 0, 1, 2
+_DTYPES = {"f32": GS_F32, "bf16": GS_BF16, "w4": GS_W4}
+GS_ESHAPE = -2
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_schedule_gamma",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -92,6 +94,10 @@ def lib():
             L.gs_profile_enable.argtypes = [C.c_void_p, C.c_int]
             L.gs_pack_weight.restype = C.c_int
             L.gs_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+            L.gs_w4_packed_bytes.restype = C.c_size_t
+            L.gs_w4_packed_bytes.argtypes = [C.c_int, C.c_int]
+            L.gs_pack_weight_w4.restype = C.c_int
+            L.gs_pack_weight_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
             L.gs_trace_residual.restype = C.c_int
             L.gs_trace_residual.argtypes = [C.c_void_p, C.c_void_p]
             L.gs_profile_read.restype = C.c_int
@@ -164,6 +170,18 @@ def gs_schedule_gamma(accepted_len, accept_stat, gamma_prev, alpha_hat, x_smooth
     return nxt
 
 
+def gs_pack_weight_w4(codes, scales, zeros, stream=None):
+    """codes uint8 [N, K], scales bf16 [N, K/128], zeros uint8 [N, K/128] (device tensors) -> packed uint8
+    device tensor in the layout the 4-bit projection kernel streams."""
+    n, k = int(codes.shape[0]), int(codes.shape[1])
+    nbytes = int(lib().gs_w4_packed_bytes(n, k))
+    if nbytes == 0:
+        raise GsError(GS_ESHAPE, "4-bit matrices need n_out to be a multiple of 64 and k_in of 128")
+    out = torch.empty(nbytes, dtype=torch.uint8, device=codes.device)
+    _check(lib().gs_pack_weight_w4(_ptr(codes), _ptr(scales), _ptr(zeros), _ptr(out), n, k, _stream(stream)))
+    return out
+
+
 def gs_pack_weight(w, stream=None):
     """Returns a new device tensor holding the [out, in] matrix `w` in the library's projection layout."""
     out = torch.empty_like(w)
@@ -176,13 +194,13 @@ class Verifier:
     """Owns a gs_ctx: model description plus device weight pointers (tensors are kept alive here)."""
 
     def __init__(self, desc: dict, top: dict, layers: list):
-        """desc: fields of gs_model_desc (dtype as 'f32' | 'bf16'); top: embed, lm_head, final_norm tensors;
+        """desc: fields of gs_model_desc (dtype as 'f32' | 'bf16' | 'w4'); top: embed, lm_head, final_norm tensors;
         layers: list of dicts wqkv, wo, wgu, wd, norm1, norm2 (device tensors)."""
         self.desc = dict(desc)
         self._keep = (top, layers)
         d = gs_model_desc(desc["n_layers"], desc["d_model"], desc["n_heads"], desc["n_kv_heads"], desc["head_dim"],
                           desc["d_ffn"], desc["vocab"], desc["rope_theta"], desc["rms_eps"],
-                          GS_BF16 if desc["dtype"] == "bf16" else GS_F32)
+                          _DTYPES[desc["dtype"]])
         n = desc["n_layers"]
         arr = {k: (C.c_void_p * n)(*[layers[l][k].data_ptr() for l in range(n)])
                for k in ("wqkv", "wo", "wgu", "wd", "norm1", "norm2")}

@@ -379,9 +379,14 @@ static GemmPlan gemm_plan(int M, int N, int K) {
   return p;
 }
 
-// Number of K splits the bf16 kernel will use for this shape (1 for fp32).
+int gemm_w4_splits(int M, int N, int K);
+gs_status launch_gemm_w4(const void* X, const void* Wpacked, float* P, int M, int N, int K, hipStream_t stream);
+
+// Number of K splits the projection kernel will use for this shape (1 for fp32).
 int gemm_splits(int dtype, int M, int N, int K) {
-  if (dtype != GS_BF16 || M <= 0) return 1;
+  if (M <= 0) return 1;
+  if (dtype == GS_W4) return gemm_w4_splits(M, N, K);
+  if (dtype != GS_BF16) return 1;
   return gemm_plan(M, N, K).splits;
 }
 
@@ -414,9 +419,11 @@ static void launch_tall(const GemmPlan& p, const bf16_t* x, const bf16_t* w, flo
   }
 }
 
-// P [splits][M][N] fp32 partial sums of X [M][K] * W[N][K]^T (W tile-packed for bf16, row-major for fp32).
+// P [splits][M][N] fp32 partial sums of X [M][K] * W[N][K]^T (W tile-packed for bf16, packed 4-bit for
+// GS_W4 with bf16 activations, row-major for fp32).
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream) {
   if (M <= 0) return GS_OK;
+  if (dtype == GS_W4) return launch_gemm_w4(X, W, P, M, N, K, stream);
   if (dtype == GS_BF16) {
     const GemmPlan p = gemm_plan(M, N, K);
     const bf16_t* x = static_cast<const bf16_t*>(X);

@@ -12,6 +12,9 @@ namespace gs {
 
 int gemm_splits(int dtype, int M, int N, int K);
 gs_status launch_pack_weight(const void* src, void* dst, int N, int K, hipStream_t stream);
+size_t w4_packed_bytes(int N, int K);
+gs_status launch_pack_weight_w4(const void* q, const void* scales, const void* zeros, void* packed, int N, int K,
+                                hipStream_t stream);
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream);
 gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
@@ -160,6 +163,20 @@ extern "C" gs_status gs_pack_weight(const void* w_rowmajor, void* w_packed, int 
   return gs::launch_pack_weight(w_rowmajor, w_packed, n_out, k_in, stream);
 }
 
+extern "C" size_t gs_w4_packed_bytes(int n_out, int k_in) {
+  if (n_out <= 0 || k_in <= 0 || n_out % 64 || k_in % 128) return 0;
+  return gs::w4_packed_bytes(n_out, k_in);
+}
+
+extern "C" gs_status gs_pack_weight_w4(const uint8_t* codes, const void* scales, const uint8_t* zeros, void* w_packed,
+                                       int n_out, int k_in, void* hip_stream) {
+  if (!codes || !scales || !zeros || !w_packed) return gs::fail(GS_EINVAL, "null argument");
+  if (n_out <= 0 || k_in <= 0) return gs::fail(GS_EINVAL, "matrix dimensions must be positive");
+  if (n_out % 64 || k_in % 128)
+    return gs::fail(GS_ESHAPE, "4-bit matrices need n_out to be a multiple of 64 and k_in of 128");
+  return gs::launch_pack_weight_w4(codes, scales, zeros, w_packed, n_out, k_in, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, gs_ctx** out) {
   if (!desc || !w || !out) return gs::fail(GS_EINVAL, "null argument");
   const gs_model_desc& m = *desc;
@@ -167,15 +184,18 @@ extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, g
       m.vocab <= 0)
     return gs::fail(GS_EINVAL, "model dimensions must be positive");
   if (m.d_model % 4) return gs::fail(GS_ESHAPE, "d_model must be a multiple of 4");
-  if (m.dtype != GS_F32 && m.dtype != GS_BF16) return gs::fail(GS_EINVAL, "dtype must be GS_F32 or GS_BF16");
+  if (m.dtype != GS_F32 && m.dtype != GS_BF16 && m.dtype != GS_W4)
+    return gs::fail(GS_EINVAL, "dtype must be GS_F32, GS_BF16 or GS_W4");
   if (m.head_dim != 64 && m.head_dim != 128) return gs::fail(GS_ESHAPE, "head_dim must be 64 or 128");
   if (m.n_heads % m.n_kv_heads != 0) return gs::fail(GS_ESHAPE, "n_heads must be a multiple of n_kv_heads");
   const int group = m.n_heads / m.n_kv_heads;
   if (group != 1 && group != 2 && group != 4 && group != 8) return gs::fail(GS_ESHAPE, "GQA group must be 1, 2, 4 or 8");
-  if (m.dtype == GS_BF16) {
+  if (m.dtype == GS_BF16 || m.dtype == GS_W4) {
     const int qkv = (m.n_heads + 2 * m.n_kv_heads) * m.head_dim;
     if (m.d_model % 64 || m.d_ffn % 64 || qkv % 64 || m.vocab % 64)
       return gs::fail(GS_ESHAPE, "bf16 models need d_model, d_ffn, projection widths and vocab to be multiples of 64");
+    if (m.dtype == GS_W4 && (m.d_model % 128 || m.d_ffn % 128 || (m.n_heads * m.head_dim) % 128))
+      return gs::fail(GS_ESHAPE, "4-bit models need d_model, d_ffn and n_heads * head_dim to be multiples of 128");
   }
   if (!(m.rope_theta > 1.f) || !(m.rms_eps >= 0.f)) return gs::fail(GS_EINVAL, "rope_theta must exceed 1, rms_eps >= 0");
   if (!w->embed || !w->lm_head || !w->final_norm || !w->wqkv || !w->wo || !w->wgu || !w->wd || !w->norm1 || !w->norm2)
@@ -195,7 +215,7 @@ extern "C" gs_status gs_create(const gs_model_desc* desc, const gs_weights* w, g
   c->wd.assign(w->wd, w->wd + m.n_layers);
   c->norm1.assign(w->norm1, w->norm1 + m.n_layers);
   c->norm2.assign(w->norm2, w->norm2 + m.n_layers);
-  c->elem = m.dtype == GS_BF16 ? 2 : 4;
+  c->elem = m.dtype == GS_F32 ? 4 : 2;
   *out = c;
   return GS_OK;
 }
@@ -288,7 +308,8 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     return gs::fail(GS_EINVAL, "null batch field");
   if (!kv->k_pages || !kv->v_pages || kv->page_size <= 0 || kv->n_pages <= 0 || b->max_blocks <= 0)
     return gs::fail(GS_EINVAL, "invalid KV cache descriptor");
-  if (m.dtype == GS_BF16 && kv->page_size % 16 != 0)
+  const int act = m.dtype == GS_W4 ? GS_BF16 : m.dtype;     // storage type of activations, KV pages, embedding
+  if (act == GS_BF16 && kv->page_size % 16 != 0)
     return gs::fail(GS_ESHAPE, "bf16 attention needs a page size that is a multiple of 16");
   long R = 0, G = 0, total_steps = 0;
   int max_t = 0, max_ctx = 0;
@@ -336,34 +357,34 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     GS_TRY(call);               \
     GS_TRY(timer.end());        \
   } while (0)
-  GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(m.dtype, ctx->embed, b->tokens, p.x, rows, d, stream));
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(act, ctx->embed, b->tokens, p.x, rows, d, stream));
   GS_STAGE(GS_STAGE_GLUE, gs::launch_row_meta(b->cu_rows, b->ctx_len, n, rows, b->block_table, b->max_blocks, kv->page_size,
                                               m.head_dim, m.rope_theta, p.row_slot, p.rope, stream));
   const float* pending = nullptr;   // split-K partials of the projection whose result is still to be added to x
   int pending_splits = 0;
   for (int l = 0; l < m.n_layers; ++l) {
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(act, p.x, pending, pending_splits, rows, ctx->norm1[l], m.rms_eps, p.h, d, stream));
     if (ctx->residual_trace)   // residual stream entering layer l (complete once the pending partials are added)
       GS_HIP_CHECK(hipMemcpyAsync(ctx->residual_trace + (size_t)l * rows * d, p.x, sizeof(float) * rows * d,
                                   hipMemcpyDeviceToDevice, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wqkv[l], p.partial, rows, qkv, d, stream));
     char* kl = static_cast<char*>(kv->k_pages) + layer_stride * l;
     char* vl = static_cast<char*>(kv->v_pages) + layer_stride * l;
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_rope_append(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, p.row_slot,
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_rope_append(act, p.partial, gs::gemm_splits(m.dtype, rows, qkv, d), rows, p.row_slot,
                                   p.rope, kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, p.q, kl, vl, stream));
-    GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(m.dtype, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
+    GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(act, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
                                 kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_sps, attn_splits,
                                 p.row_slot, p.attn_scratch, p.attn, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(act, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
                                                    ctx->norm2[l], m.rms_eps, p.h, d, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_swiglu(m.dtype, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_swiglu(act, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.act, ctx->wd[l], p.partial, rows, d, F, stream));
     pending = p.partial;
     pending_splits = gs::gemm_splits(m.dtype, rows, d, F);
   }
-  GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(m.dtype, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(act, p.x, pending, pending_splits, rows, ctx->final_norm, m.rms_eps, p.h, d, stream));
   if (ctx->residual_trace)
     GS_HIP_CHECK(hipMemcpyAsync(ctx->residual_trace + (size_t)m.n_layers * rows * d, p.x, sizeof(float) * rows * d,
                                 hipMemcpyDeviceToDevice, stream));

@@ -275,6 +275,27 @@ def layer_weights(ms: ModelShape, seed, layer, std=0.02):
     return out
 
 
+W4_GROUP = 128
+
+
+def quantize_w4(w, group=W4_GROUP):
+    """Synthetic 4-bit checkpoint of a float matrix [N, K]: per row and group of `group` inputs an asymmetric
+    min/max grid that contains zero.  Returns (codes uint8 [N, K] in 0..15, scales float32 [N, K/group]
+    holding bf16 values, zeros uint8 [N, K/group] in 0..15).  This only manufactures inputs; what the
+    verifier computes from them is defined on the two sides separately."""
+    w = np.asarray(w, dtype=np.float32)
+    n, k = w.shape
+    assert k % group == 0
+    g = w.reshape(n, k // group, group)
+    lo = np.minimum(g.min(axis=2), 0.0)
+    hi = np.maximum(g.max(axis=2), 0.0)
+    scale = round_to_bf16(((hi - lo) / 15.0).astype(np.float32))
+    scale = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    zero = np.clip(np.rint(-lo / scale), 0, 15).astype(np.uint8)
+    codes = np.clip(np.rint(g / scale[:, :, None]) + zero[:, :, None], 0, 15).astype(np.uint8)
+    return codes.reshape(n, k), scale, zero
+
+
 def top_weights(ms: ModelShape, seed, std=0.02):
     return {
         "embed": matrix(ms, seed, "embed", 0, (ms.vocab, ms.d_model), std),

@@ -17,7 +17,8 @@ def _dev():
 
 
 def storage_dtype(ms: synth.ModelShape):
-    return torch.bfloat16 if ms.dtype == "bf16" else torch.float32
+    """Storage type of activations, KV pages and the embedding table."""
+    return torch.float32 if ms.dtype == "f32" else torch.bfloat16
 
 
 def to_device(a, dtype):
@@ -30,9 +31,17 @@ def _progress(msg):
 
 
 def upload_model(ms: synth.ModelShape, top: dict, get_layer, progress=False):
-    """Returns a binding.Verifier for weights given as float32 numpy arrays."""
+    """Returns a binding.Verifier for weights given as float32 numpy arrays (for ms.dtype "w4" the projection
+    matrices are given as (codes, scales, zeros) triples instead)."""
     dt = storage_dtype(ms)
-    packed = lambda a: gsb.gs_pack_weight(to_device(a, dt))      # the row-major upload is dropped after the repack
+    if ms.dtype == "w4":
+        # a projection matrix arrives as a 4-bit checkpoint triple (codes, scales, zeros), see synth.quantize_w4
+        def packed(t):
+            codes, scales, zeros = t
+            return gsb.gs_pack_weight_w4(to_device(codes, torch.uint8), to_device(scales, torch.bfloat16),
+                                         to_device(zeros, torch.uint8))
+    else:
+        packed = lambda a: gsb.gs_pack_weight(to_device(a, dt))      # the row-major upload is dropped after the repack
     top_d = {"embed": to_device(top["embed"], dt), "lm_head": packed(top["lm_head"]),
              "final_norm": to_device(top["final_norm"], torch.float32)}
     layers = []

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "goodspeed.h")).read()
-    declared = set(re.findall(r"\b(gs_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(gs_[a-z0-9_]+)\s*\(", header))
     assert declared == set(gsb.EXPORTS)
     L = gsb.lib()
     for name in declared:
