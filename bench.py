@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (result is marked invalid)")
-    ap.add_argument("--workload", choices=["cfg3", "cfg4", "cfg5", "rows1024"], default="cfg3",
+    ap.add_argument("--workload", choices=["cfg3", "cfg4", "cfg5", "cfg3w4", "cfg5w4", "rows1024"], default="cfg3",
                     help="cfg3 (default) is the configuration the metric is quoted on; cfg4 (32 ragged servers, "
                          "paged) and cfg5 (70B shape) are extra measurements")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -63,6 +63,9 @@ WORKLOADS = {
             "permuted 16-token KV pages",
     "cfg5": "llama3-70b-shaped verify (80 layers, d 8192, 64q/8kv heads, ffn 28672, vocab 128256), "
             "16 draft servers, gamma U[2,8], ctx 4096",
+    "cfg3w4": "cfg3 with 4-bit projection weights (groups of 128, synthetic checkpoint of the same random model); "
+              "not the configuration the metric is quoted on",
+    "cfg5w4": "cfg5 (70B shape) with 4-bit projection weights, the format family of the paper's larger verifier",
     "rows1024": "llama3-8b-shaped verify at a compute-bound row count: 8 servers x 128-row blocks on an empty "
                 "cache (1024 target rows); not the paper's operating point, shows the projection kernel "
                 "against the MFMA peak",
@@ -72,7 +75,7 @@ WORKLOADS = {
 def build_workload(ms, seed, name="cfg3"):
     import torch
     from paper_2512_09963_amd import synth, workload as wl
-    cfg = {"cfg3": synth.config3, "cfg4": synth.config4, "cfg5": synth.config5,
+    cfg = {"cfg3": synth.config3, "cfg4": synth.config4, "cfg5": synth.config5, "cfg3w4": synth.config3, "cfg5w4": synth.config5,
            "rows1024": synth.config_rows1024}[name](seed, ms)
     t0 = time.time()
     ver, kv, db = wl.upload_config(cfg, progress=True)
@@ -83,8 +86,13 @@ def build_workload(ms, seed, name="cfg3"):
 
 
 def projection_weight_bytes(ms):
+    """Bytes of all projection matrices as stored: 2 per weight for bf16; for the 4-bit format half a byte per
+    weight plus one 4-byte word of scale and zero point per output row and group of 128 inputs."""
     per_layer = ms.qkv_out * ms.d_model + ms.d_model * ms.n_heads * ms.head_dim + 3 * ms.d_ffn * ms.d_model
-    return 2 * (ms.n_layers * per_layer + ms.vocab * ms.d_model)
+    n_weights = ms.n_layers * per_layer + ms.vocab * ms.d_model
+    if ms.dtype == "w4":
+        return n_weights // 2 + n_weights // 128 * 4
+    return 2 * n_weights
 
 
 def run_steps(w, n_steps, sched):
@@ -202,7 +210,9 @@ def main():
         sys.exit(1)
     gsb.lib()
     seed = synth.MASTER_SEED
-    ms = synth.LLAMA3_70B if args.workload == "cfg5" else synth.LLAMA3_8B
+    ms = synth.LLAMA3_70B if args.workload in ("cfg5", "cfg5w4") else synth.LLAMA3_8B
+    if args.workload in ("cfg3w4", "cfg5w4"):
+        ms = dataclasses.replace(ms, dtype="w4")
     if args.layers:
         ms = dataclasses.replace(ms, n_layers=args.layers)
     w = build_workload(ms, seed, args.workload)
@@ -257,7 +267,8 @@ def main():
     res = {
         "metric": "verified_tokens_per_s", "value": round(db.n_draft / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 (4-bit weights)" if ms.dtype == "w4" else "bf16", "data": "synthetic",
         "config": {"workload": WORKLOADS[args.workload],
                    "n_servers": db.n_servers, "draft_tokens": db.n_draft, "target_rows": db.n_rows,
                    "gamma": [int(g) for g in db.gamma]},

@@ -2,20 +2,23 @@
 // the AWQ checkpoints the paper's 70B verifier uses, Section IV-A): Y = X * W^T with
 // W[n][k] = (code[n][k] - zero[n][k/128]) * scale[n][k/128], codes and zeros in 0..15, scales bf16.
 //
-// Same streaming design as the bf16 kernel, with a quarter of the weight bytes: a wave owns 16 output
-// columns and reads, per 64-wide k step, 8 bytes per lane (16 codes of one column) plus one 32-bit word
-// with the column's scale and zero point; the codes are turned into bf16 in registers and fed to the MFMA
-// as the B operand.  Dequantisation: the code c becomes the bf16 bit pattern 0x4300 + c = 128 + c (exact),
-// widened to fp32, then fma(128 + c, scale, -(128 + zero) * scale) = (c - zero) * scale, which is exact in
-// fp32 (5 x 8 significant bits), and rounded to bf16 (nearest even) by the packed conversion: every
-// dequantised weight is a function of (c, zero, scale) alone, the same on every path.
+// Same streaming design as the bf16 kernel, with a quarter of the weight bytes, which moves the bound from
+// HBM to the dequantisation arithmetic and the MFMA pipe; so the kernel uses the 32x32x16 MFMA (twice the
+// issue rate of the 16x16x32 one on this chip): a wave owns 32 output columns and up to 128 rows and reads,
+// per 64-wide k step, 16 bytes per lane (32 codes of one column) plus one 32-bit word with the column's
+// scale and zero point; the codes are turned into bf16 in registers and fed to the MFMA as the B operand.
+// Dequantisation: four codes are spread to the bytes of a word (two mask operations per eight codes), each
+// byte is converted to fp32 by the byte-conversion instruction, fma(c, scale, -zero * scale) = (c - zero) *
+// scale is exact in fp32 (5 x 8 significant bits), and the packed conversion rounds it to bf16 (nearest
+// even): every dequantised weight is a function of (c, zero, scale) alone, the same on every path.
 //
 // Packed layout (gs_pack_weight_w4):
-//   codes [K/64][N/16][64 lanes][2 words]: lane l = 16 g + c holds column c, inputs 16 g .. 16 g + 15; word 0
-//         the first 8, word 1 the last 8; in a word, input 2p sits in bits 4p..4p+3 and input 2p+1 in bits
-//         16+4p..16+4p+3, so that (word >> 4p) & 0x000F000F is one bf16 pair's worth of codes
+//   codes [K/64][N/32][64 lanes][4 words]: lane l holds column l%32, and word kg holds inputs
+//         16 kg + 8 (l/32) + i, i = 0..7 (the B fragment of k group kg); in a word, codes 0..3 sit in the low
+//         nibbles of bytes 0..3 and codes 4..7 in the high nibbles, so that (word & 0x0F0F0F0F) and
+//         ((word >> 4) & 0x0F0F0F0F) each hold four codes, one per byte
 //   meta  [K/128][N] words: bf16 scale in the high half, zero point in the low byte
-// Activations go through LDS exactly as in the bf16 kernel.  Rows beyond 64 are served in chunks of 64 by
+// Activations go through LDS exactly as in the bf16 kernels.  Rows beyond 128 are served in chunks of 128 by
 // separate workgroups (XCD-aware order, see the bf16 kernel); a taller tile is not built for this format.
 #include "common.h"
 #include "device_types.h"
@@ -28,51 +31,62 @@ constexpr int kLdsRow = kBK + 8;
 constexpr int kGroup = 128;
 constexpr int kDepth = 4;
 
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+
 struct W4Step {
-  uint2 codes;
+  uint4 codes;       // word kg = the 8 codes of k group kg
   uint32_t meta;
 };
 
-__device__ __forceinline__ bf16x8_t dequant8(uint32_t word, float scale, float neg_c0) {
+// word: codes 0..3 in the even nibbles of bytes 0..3, codes 4..7 in the odd nibbles
+__device__ __forceinline__ bf16x8_t dequant8(uint32_t word, float scale, float neg_zs) {
+  const uint32_t lo4 = word & 0x0F0F0F0Fu, hi4 = (word >> 4) & 0x0F0F0F0Fu;
+  float f[8];
+  f[0] = (float)(lo4 & 0xffu);
+  f[1] = (float)((lo4 >> 8) & 0xffu);
+  f[2] = (float)((lo4 >> 16) & 0xffu);
+  f[3] = (float)(lo4 >> 24);
+  f[4] = (float)(hi4 & 0xffu);
+  f[5] = (float)((hi4 >> 8) & 0xffu);
+  f[6] = (float)((hi4 >> 16) & 0xffu);
+  f[7] = (float)(hi4 >> 24);
   uint4 out;
-  uint32_t* o = reinterpret_cast<uint32_t*>(&out);
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const uint32_t pair = ((word >> (4 * p)) & 0x000F000Fu) | 0x43004300u;     // (128 + c_even, 128 + c_odd) as bf16
-    const float lo = fmaf(__uint_as_float(pair << 16), scale, neg_c0);
-    const float hi = fmaf(__uint_as_float(pair & 0xffff0000u), scale, neg_c0);
-    o[p] = pack_bf16x2(lo, hi);
-  }
+  out.x = pack_bf16x2(fmaf(f[0], scale, neg_zs), fmaf(f[1], scale, neg_zs));
+  out.y = pack_bf16x2(fmaf(f[2], scale, neg_zs), fmaf(f[3], scale, neg_zs));
+  out.z = pack_bf16x2(fmaf(f[4], scale, neg_zs), fmaf(f[5], scale, neg_zs));
+  out.w = pack_bf16x2(fmaf(f[6], scale, neg_zs), fmaf(f[7], scale, neg_zs));
   return *reinterpret_cast<const bf16x8_t*>(&out);
 }
 
-template <int MT, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_w4_skinny_kernel(const bf16_t* __restrict__ X,
-                                                                 const uint2* __restrict__ codes,
-                                                                 const uint32_t* __restrict__ meta,
-                                                                 float* __restrict__ P, int M, int N, int K,
-                                                                 int k_per_split, int m_chunks) {
-  __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
+// MT32 row tiles of 32 rows per workgroup (1, 2 or 4), NW waves of 32 columns each.
+template <int MT32, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restrict__ X,
+                                                          const uint4* __restrict__ codes,
+                                                          const uint32_t* __restrict__ meta,
+                                                          float* __restrict__ P, int M, int N, int K,
+                                                          int k_per_split, int m_chunks) {
+  constexpr int ROWS = MT32 * 32;
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][ROWS * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 4, c = lane & 15;
+  const int h = lane >> 5, c32 = lane & 31;
   int n_block = blockIdx.x, m_chunk = 0;
   if (m_chunks > 1) {
     const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
     m_chunk = t % m_chunks;
     n_block = (t / m_chunks) * 8 + xcd;
-    if (n_block * (16 * NW) >= N) return;
+    if (n_block * (32 * NW) >= N) return;
   }
-  const int n_tile = n_block * NW + wave;
-  const int n0 = n_tile * 16;
+  const int n_tile = n_block * NW + wave;        // 32-column tile
+  const int n0 = n_tile * 32;
   const int split = blockIdx.y;
-  const int m0 = m_chunk * (MT * 16);
+  const int m0 = m_chunk * ROWS;
   const int k_begin = split * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
   const int n_steps = (k_end - k_begin) / kBK;
   const int step0 = k_begin / kBK;
 
   constexpr int kThreads = 64 * NW;
-  constexpr int kChunks = MT * 128;
+  constexpr int kChunks = ROWS * 8;
   constexpr int kPasses = (kChunks + kThreads - 1) / kThreads;
   uint4 xreg[kDepth][kPasses];
   auto load_x = [&](int slot, int step) {
@@ -94,24 +108,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_skinny_kernel(const bf16_t* _
       if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[slot][p];
     }
   };
-  const size_t code_stride = (size_t)(N / 16) * 64;       // uint2 per k step
-  const uint2* cbase = codes + (size_t)step0 * code_stride + (size_t)n_tile * 64 + lane;
-  const uint32_t* mbase = meta + n0 + c;
+  const size_t code_stride = (size_t)(N / 32) * 64;       // uint4 per k step
+  const uint4* cbase = codes + (size_t)step0 * code_stride + (size_t)n_tile * 64 + lane;
+  const uint32_t* mbase = meta + n0 + c32;
   W4Step wreg[kDepth];
   auto load_w = [&](int slot, int step) {
     wreg[slot].codes = cbase[(size_t)step * code_stride];
     wreg[slot].meta = mbase[(size_t)((step0 + step) >> 1) * N];
   };
 
-  floatx4_t acc[MT];
+  floatx16_t acc[MT32];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MT32; ++mt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[mt][e] = 0.f;
 #pragma unroll
   for (int d = 0; d < kDepth; ++d)
     if (d < n_steps) {
       load_w(d, d);
       load_x(d, d);
     }
+  // A fragment of row tile mt, k group kg: row mt*32 + lane%32, 16-byte piece 2 kg + lane/32
+  const int a_lane = c32 * kLdsRow + h * 8;
   for (int base = 0; base < n_steps; base += kDepth) {
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
@@ -126,29 +144,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_skinny_kernel(const bf16_t* _
           load_x(d, step + kDepth);
         }
         const float scale = __uint_as_float(w.meta & 0xffff0000u);
-        const float neg_c0 = -(128.0f + (float)(w.meta & 0xffu)) * scale;
-        const bf16x8_t b0 = dequant8(w.codes.x, scale, neg_c0);
-        const bf16x8_t b1 = dequant8(w.codes.y, scale, neg_c0);
+        const float neg_zs = -(float)(w.meta & 0xffu) * scale;
+        const uint32_t cw[4] = {w.codes.x, w.codes.y, w.codes.z, w.codes.w};
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const bf16_t* ap = &xs[buf][(mt * 16 + c) * kLdsRow + g * 16];
-          const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(ap);
-          const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(ap + 8);
-          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0, acc[mt], 0, 0, 0);
-          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, acc[mt], 0, 0, 0);
+        for (int kg = 0; kg < 4; ++kg) {
+          const bf16x8_t b = dequant8(cw[kg], scale, neg_zs);
+#pragma unroll
+          for (int mt = 0; mt < MT32; ++mt) {
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&xs[buf][mt * 32 * kLdsRow + a_lane + kg * 16]);
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
+          }
         }
       }
     }
   }
   float* out = P + (size_t)split * M * N;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < MT32; ++mt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = m0 + mt * 16 + g * 4 + i;
-      if (row < M) out[(size_t)row * N + n0 + c] = acc[mt][i];
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + mt * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+      if (row < M) out[(size_t)row * N + n0 + c32] = acc[mt][v];
     }
-  }
 }
 
 // One thread per packed code word (8 codes of one column) or per meta word.
@@ -159,17 +176,17 @@ __global__ __launch_bounds__(256) void pack_w4_kernel(const uint8_t* __restrict_
   const size_t n_code_words = (size_t)N * K / 8;
   const size_t n_meta = (size_t)(K / kGroup) * N;
   if (idx < n_code_words) {
-    const int half = (int)(idx & 1), lane = (int)((idx >> 1) & 63);
-    const size_t block = idx >> 7;
-    const int n_tiles = N / 16;
+    const int kg = (int)(idx & 3), lane = (int)((idx >> 2) & 63);
+    const size_t block = idx >> 8;
+    const int n_tiles = N / 32;
     const int n_tile = (int)(block % n_tiles), k_step = (int)(block / n_tiles);
-    const int g = lane >> 4, c = lane & 15;
-    const uint8_t* src = q + (size_t)(n_tile * 16 + c) * K + k_step * kBK + g * 16 + half * 8;
+    const int h = lane >> 5, c32 = lane & 31;
+    const uint8_t* src = q + (size_t)(n_tile * 32 + c32) * K + k_step * kBK + kg * 16 + h * 8;
     uint32_t w = 0;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      w |= (uint32_t)(src[2 * p] & 15u) << (4 * p);
-      w |= (uint32_t)(src[2 * p + 1] & 15u) << (16 + 4 * p);
+    for (int i = 0; i < 4; ++i) {
+      w |= (uint32_t)(src[i] & 15u) << (8 * i);            // codes 0..3: even nibbles
+      w |= (uint32_t)(src[4 + i] & 15u) << (8 * i + 4);    // codes 4..7: odd nibbles
     }
     codes[idx] = w;
   } else if (idx < n_code_words + n_meta) {
@@ -197,18 +214,17 @@ gs_status launch_pack_weight_w4(const void* q, const void* scales, const void* z
   return GS_OK;
 }
 
-// Launch shape of the 4-bit kernel: row tiles per workgroup (1, 2 or 4), row chunks of 64, waves, K splits.
+// Launch shape of the 4-bit kernel: 32-row tiles per workgroup (1, 2 or 4), row chunks of 128, waves, K splits.
 struct W4Plan {
-  int mt, m_chunks, waves, splits, k_per;
+  int mt32, m_chunks, waves, splits, k_per;
 };
 
 static W4Plan w4_plan(int M, int N, int K) {
   W4Plan p;
-  const int tiles = ceil_div(M, 16);
-  p.mt = tiles <= 1 ? 1 : tiles <= 2 ? 2 : 4;
-  p.m_chunks = ceil_div(tiles, p.mt);
-  p.waves = (N % 128 == 0 && N / 128 >= 192) ? 8 : 4;
-  const int wgs = N / (16 * p.waves) * p.m_chunks;
+  p.mt32 = M <= 32 ? 1 : M <= 64 ? 2 : 4;
+  p.m_chunks = ceil_div(M, 32 * p.mt32);
+  p.waves = (N % 256 == 0 && N / 256 >= 96) ? 8 : (N % 128 == 0 ? 4 : 2);
+  const int wgs = N / (32 * p.waves) * p.m_chunks;
   int want = (512 + wgs / 2) / wgs;
   const int max_s = K / 512 > 0 ? K / 512 : 1;
   int s = want < max_s ? want : max_s;
@@ -221,16 +237,17 @@ static W4Plan w4_plan(int M, int N, int K) {
 int gemm_w4_splits(int M, int N, int K) { return M <= 0 ? 1 : w4_plan(M, N, K).splits; }
 
 template <int NW>
-static void launch_w4(const W4Plan& p, const bf16_t* x, const uint2* codes, const uint32_t* meta, float* P, int M,
+static void launch_w4(const W4Plan& p, const bf16_t* x, const uint4* codes, const uint32_t* meta, float* P, int M,
                       int N, int K, hipStream_t stream) {
-  const int n_blocks = N / (16 * NW);
+  const int n_blocks = N / (32 * NW);
   const int gx = p.m_chunks > 1 ? ceil_div(n_blocks, 8) * 8 * p.m_chunks : n_blocks;
   const dim3 grid(gx, p.splits, 1);
-  switch (p.mt) {
-    case 1: gemm_w4_skinny_kernel<1, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks); break;
-    case 2: gemm_w4_skinny_kernel<2, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks); break;
-    default: gemm_w4_skinny_kernel<4, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
-  }
+  if (p.mt32 == 1)
+    gemm_w4_kernel<1, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+  else if (p.mt32 == 2)
+    gemm_w4_kernel<2, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+  else
+    gemm_w4_kernel<4, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
 }
 
 // P [splits][M][N] fp32 partial sums of X [M][K] (bf16) * W^T with W given in the packed 4-bit layout.
@@ -238,10 +255,11 @@ gs_status launch_gemm_w4(const void* X, const void* Wpacked, float* P, int M, in
   if (M <= 0) return GS_OK;
   const W4Plan p = w4_plan(M, N, K);
   const bf16_t* x = static_cast<const bf16_t*>(X);
-  const uint2* codes = static_cast<const uint2*>(Wpacked);
+  const uint4* codes = static_cast<const uint4*>(Wpacked);
   const uint32_t* meta = reinterpret_cast<const uint32_t*>(static_cast<const char*>(Wpacked) + w4_code_bytes(N, K));
   if (p.waves == 8) launch_w4<8>(p, x, codes, meta, P, M, N, K, stream);
-  else launch_w4<4>(p, x, codes, meta, P, M, N, K, stream);
+  else if (p.waves == 4) launch_w4<4>(p, x, codes, meta, P, M, N, K, stream);
+  else launch_w4<2>(p, x, codes, meta, P, M, N, K, stream);
   GS_LAUNCH_CHECK("gemm_w4");
   return GS_OK;
 }

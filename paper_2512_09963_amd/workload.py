@@ -22,6 +22,8 @@ def storage_dtype(ms: synth.ModelShape):
 
 
 def to_device(a, dtype):
+    if isinstance(a, torch.Tensor):
+        return a.to(_dev()).to(dtype)
     return torch.from_numpy(np.ascontiguousarray(a)).to(_dev()).to(dtype)
 
 
@@ -112,17 +114,42 @@ def verify(ver: gsb.Verifier, kv: KVCache, db: DeviceBatch, workspace=None, want
     return out, logits, workspace
 
 
+def quantize_w4_device(w):
+    """synth.quantize_w4 with torch ops on the device (same float32 arithmetic, so the same checkpoint):
+    used for full-size synthetic models, where the host version takes minutes.  w: float32 numpy [N, K]."""
+    g = synth.W4_GROUP
+    t = torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(_dev())
+    n, k = t.shape
+    tg = t.view(n, k // g, g)
+    lo = torch.clamp(tg.amin(dim=2), max=0.0)
+    hi = torch.clamp(tg.amax(dim=2), min=0.0)
+    scale = ((hi - lo) / 15.0).to(torch.bfloat16).to(torch.float32)
+    scale = torch.where(scale > 0, scale, torch.ones_like(scale))
+    zero = torch.clamp(torch.round(-lo / scale), 0, 15)
+    codes = torch.clamp(torch.round(tg / scale[:, :, None]) + zero[:, :, None], 0, 15)
+    return codes.view(n, k).to(torch.uint8), scale, zero.to(torch.uint8)
+
+
 def upload_config(cfg: synth.VerifyConfig, ver=None, progress=False):
-    """Device side of a synth.VerifyConfig: model (random init from the seed), synthetic KV, batch."""
+    """Device side of a synth.VerifyConfig: model (random init from the seed), synthetic KV, batch.
+    For ms.dtype "w4" the random bf16 matrices are turned into a synthetic 4-bit checkpoint first."""
+    import dataclasses
     ms, seed, batch = cfg.ms, cfg.seed, cfg.batch
+    gen = dataclasses.replace(ms, dtype="bf16") if ms.dtype == "w4" else ms      # what the generators see
     if ver is None:
-        top = synth.top_weights(ms, seed)
-        ver = upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l), progress)
+        top = synth.top_weights(gen, seed)
+        if ms.dtype == "w4":
+            def quantized(W):
+                return {k: (quantize_w4_device(v) if k in ("wqkv", "wo", "wgu", "wd", "lm_head") else v)
+                        for k, v in W.items()}
+            ver = upload_model(ms, quantized(top), lambda l: quantized(synth.layer_weights(gen, seed, l)), progress)
+        else:
+            ver = upload_model(ms, top, lambda l: synth.layer_weights(ms, seed, l), progress)
         del top
     kv = KVCache(ms, batch.n_pages, batch.page_size, zero=False)
     for l in range(ms.n_layers):
-        kv.set_layer(l, synth.kv_layer_cache(ms, seed, l, "k", batch.n_pages, batch.page_size),
-                     synth.kv_layer_cache(ms, seed, l, "v", batch.n_pages, batch.page_size))
+        kv.set_layer(l, synth.kv_layer_cache(gen, seed, l, "k", batch.n_pages, batch.page_size),
+                     synth.kv_layer_cache(gen, seed, l, "v", batch.n_pages, batch.page_size))
         if progress and (l + 1) % 16 == 0:
             _progress(f"[workload] KV of {l + 1}/{ms.n_layers} layers in place")
     db = DeviceBatch(batch, cfg.tokens, cfg.q_probs, cfg.u_accept, cfg.u_resample)
