@@ -26,8 +26,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "5a0d095b50f2b7dc1ae9ff36abda53e1dbfece7dc34dede7b733d0afea4e72f6",
-                "bytes_per_launch": 129643895}
+GEMM_TRAFFIC = {"gemm_hip_sha256": "1263147a89481c67422e20b6abdd5e4547b57af835e30b8fe7dfada7245de6ae",
+                "bytes_per_launch": 129640983}
 
 
 def measured_traffic():
