@@ -118,11 +118,70 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 // partial_o [R][H][max_splits][HD] fp32, partial_ml [R][H][max_splits][2]; splits beyond a server's own
 // count are never written and never read.
 // ------------------------------------------------------------------------------------------
+// Work list of a step: one entry per (server, split) that has keys, so that the grid holds no workgroup
+// that starts only to find its split empty (ragged contexts), and an entry carries all a workgroup needs
+// before its first load, the pages of its first step included: start-up costs one dependent read instead
+// of three.  list = int header[8] (header[0] = number of entries), then the entries.
+struct AttnWork {
+  int srv, split, row0, n_tokens, ctx, page0, page1, pad;
+};
+static_assert(sizeof(AttnWork) == 32, "entries are read as one 32-byte load");
+
+// One workgroup; a lane owns a server (in rounds of 256 servers), a scan over the servers' split counts
+// gives the position of its entries.  Entries beyond the capacity are dropped (cannot happen when the
+// host's copy of the batch geometry matches the device's).
+__global__ __launch_bounds__(256) void attn_work_kernel(const int* __restrict__ cu_rows,
+                                                        const int* __restrict__ ctx_len, int n_servers,
+                                                        const int* __restrict__ block_table, int max_blocks,
+                                                        int page_size, int steps_per_split, int capacity,
+                                                        int* __restrict__ list) {
+  __shared__ int scan[256];
+  __shared__ int base_sh;
+  const int tid = threadIdx.x;
+  if (tid == 0) base_sh = 0;
+  __syncthreads();
+  AttnWork* entries = reinterpret_cast<AttnWork*>(list + 8);
+  for (int c0 = 0; c0 < n_servers; c0 += 256) {
+    const int srv = c0 + tid;
+    int count = 0, row0 = 0, T = 0, L = 0;
+    if (srv < n_servers) {
+      row0 = cu_rows[srv];
+      T = cu_rows[srv + 1] - row0;
+      L = ctx_len[srv];
+      count = (((L + T + 31) >> 5) + steps_per_split - 1) / steps_per_split;
+    }
+    scan[tid] = count;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+      const int v = tid >= off ? scan[tid - off] : 0;
+      __syncthreads();
+      scan[tid] += v;
+      __syncthreads();
+    }
+    const int first = base_sh + scan[tid] - count;
+    const int last_tile_key = ((L + T - 1) >> 4) << 4;
+    for (int s = 0; s < count && first + s < capacity; ++s) {
+      AttnWork w;
+      w.srv = srv; w.split = s; w.row0 = row0; w.n_tokens = T; w.ctx = L; w.pad = 0;
+      const int key0 = min(s * steps_per_split * 32, last_tile_key), key1 = min(key0 + 16, last_tile_key);
+      w.page0 = block_table[(size_t)srv * max_blocks + key0 / page_size];
+      w.page1 = block_table[(size_t)srv * max_blocks + key1 / page_size];
+      entries[first + s] = w;
+    }
+    __syncthreads();
+    if (tid == 255) base_sh += scan[255];
+    __syncthreads();
+  }
+  if (tid == 0) list[0] = min(base_sh, capacity);
+}
+
 __device__ __forceinline__ void wait_all_vector_loads() {
   // s_waitcnt vmcnt(0) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8;
   // the other two fields at their maximum mean "do not wait")
   __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));
 }
+
+typedef unsigned int uintx2_t __attribute__((ext_vector_type(2)));
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 
@@ -135,13 +194,14 @@ __device__ __forceinline__ float halves_sum(float x) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// (164 vector registers: three waves per SIMD, i.e. up to four 3-wave workgroups per CU, which hides a
+// workgroup's start-up and barrier stalls behind the others' loads)
 template <int HD, int G, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 2 : 3))) void attn_kernel(const bf16_t* __restrict__ q,
                                                          const bf16_t* __restrict__ k_pages,
                                                          const bf16_t* __restrict__ v_pages,
                                                          const int* __restrict__ block_table, int max_blocks,
-                                                         const int* __restrict__ cu_rows,
-                                                         const int* __restrict__ ctx_len, int page_size,
+                                                         const int* __restrict__ work, int page_size,
                                                          int n_heads, int n_kv, int steps_per_split,
                                                          int max_splits, int q_row_offset,
                                                          float* __restrict__ partial_o,
@@ -153,14 +213,16 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict_
   constexpr int STAGE = 4 * PART;        // K tile 0, K tile 1, V tile 0, V tile 1
   __shared__ __attribute__((aligned(16))) unsigned char ring[2 * STAGE];
 
-  const int split = blockIdx.x, kh = blockIdx.y, srv = blockIdx.z;
+  const int kh = blockIdx.y;
+  // (the grid never exceeds the list's capacity, so the entry may be read before the count is known)
+  const AttnWork wk = *reinterpret_cast<const AttnWork*>(work + 8 + 8 * blockIdx.x);
+  if ((int)blockIdx.x >= work[0]) return;
+  const int srv = wk.srv, split = wk.split, row0 = wk.row0, T = wk.n_tokens, L = wk.ctx;
+  const int first_pages[2] = {wk.page0, wk.page1};
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = lane >> 5, c32 = lane & 31;
-  const int g = lane >> 4, c = lane & 15;            // loader roles (same as the 16-row kernel)
-  const int row0 = cu_rows[srv];
-  const int T = cu_rows[srv + 1] - row0;
-  const int L = ctx_len[srv];
+  const int g = lane >> 4, c = lane & 15;            // loader roles
   const int n_keys = L + T;
   const int n_steps_all = (n_keys + 31) >> 5;
   const int step_begin = split * steps_per_split;
@@ -199,14 +261,20 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict_
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
 
-  auto lookup = [&](int step, int (&page)[2], int (&slot0)[2]) {
+  // block-table entry and first slot of the two 16-key tiles of a step (a tile past the end re-reads the last one)
+  auto locate = [&](int step, int (&blk)[2], int (&slot0)[2]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int key0 = min(step * 32 + t * 16, last_tile_key);
-      const int blk = page_pow2 ? key0 >> page_shift : key0 / page_size;
-      page[t] = bt[blk];
-      slot0[t] = key0 - blk * page_size;
+      blk[t] = page_pow2 ? key0 >> page_shift : key0 / page_size;
+      slot0[t] = key0 - blk[t] * page_size;
     }
+  };
+  auto lookup = [&](int step, int (&page)[2], int (&slot0)[2]) {
+    int blk[2];
+    locate(step, blk, slot0);
+    page[0] = bt[blk[0]];
+    page[1] = bt[blk[1]];
   };
   const unsigned k_lane_off = (unsigned)(c * HD + g * 8) * 2u;
   const unsigned v_lane_off = (unsigned)((lane >> 1) * page_size + (lane & 1) * 8) * 2u;
@@ -239,8 +307,11 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict_
   };
 
   int pg_next[2], sl_next[2];
-  lookup(step_begin, pg_next, sl_next);
-  issue(0, pg_next, sl_next);
+  {
+    int blk[2];
+    locate(step_begin, blk, sl_next);
+    issue(0, first_pages, sl_next);
+  }
   if (1 < n) lookup(step_begin + 1, pg_next, sl_next);
 
   // K fragment of k step kk for this lane: tile c32/16, fragment kk/2, lane group 2 (kk%2) + h, key c32%16
@@ -332,41 +403,51 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const bf16_t* __restrict_
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[dt][e] *= corr;
     }
-    // second product
-    uint4 vv[DT][2];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const unsigned char* vp = base + v_lane + kk * PART + dt * 1024;
-        const uint2 a = *reinterpret_cast<const uint2*>(vp);
-        const uint2 b = *reinterpret_cast<const uint2*>(vp + 16);
-        vv[dt][kk] = make_uint4(a.x, a.y, b.x, b.y);
-      }
-    if (step * 32 + 32 > n_keys) {
+    // second product, two channel tiles at a time (16 fragment registers live instead of 32)
+    const bool tail = step * 32 + 32 > n_keys;
+    uint4 keep[2];
+    if (tail) {
       // keys past the end of the sequence inside the last page hold stale data: zero their V
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
         const int kb0 = step * 32 + 16 * kk + 4 * h, kb1 = kb0 + 8;
-        uint4 keep;
-        keep.x = (kb0 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 1 < n_keys ? 0xffff0000u : 0u);
-        keep.y = (kb0 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 3 < n_keys ? 0xffff0000u : 0u);
-        keep.z = (kb1 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 1 < n_keys ? 0xffff0000u : 0u);
-        keep.w = (kb1 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 3 < n_keys ? 0xffff0000u : 0u);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          vv[dt][kk].x &= keep.x; vv[dt][kk].y &= keep.y; vv[dt][kk].z &= keep.z; vv[dt][kk].w &= keep.w;
-        }
+        keep[kk].x = (kb0 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 1 < n_keys ? 0xffff0000u : 0u);
+        keep[kk].y = (kb0 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb0 + 3 < n_keys ? 0xffff0000u : 0u);
+        keep[kk].z = (kb1 + 0 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 1 < n_keys ? 0xffff0000u : 0u);
+        keep[kk].w = (kb1 + 2 < n_keys ? 0x0000ffffu : 0u) | (kb1 + 3 < n_keys ? 0xffff0000u : 0u);
       }
     }
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+    for (int d0 = 0; d0 < DT; d0 += 2) {
+      uint4 vv[2][2];
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv[dt][kk]);
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kk], oacc[dt], 0, 0, 0);
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo[kk], oacc[dt], 0, 0, 0);
+      for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          const unsigned char* vp = base + v_lane + kk * PART + (d0 + dd) * 1024;
+          // (native vector type: an LDS read without type metadata makes the compiler wait for every
+          // outstanding global->LDS load first, which would drain the prefetched stage in mid-step)
+          const uintx2_t a = *reinterpret_cast<const uintx2_t*>(vp);
+          const uintx2_t b = *reinterpret_cast<const uintx2_t*>(vp + 16);
+          vv[dd][kk] = make_uint4(a.x, a.y, b.x, b.y);
+        }
+      if (tail) {
+#pragma unroll
+        for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            vv[dd][kk].x &= keep[kk].x; vv[dd][kk].y &= keep[kk].y; vv[dd][kk].z &= keep[kk].z; vv[dd][kk].w &= keep[kk].w;
+          }
       }
+#pragma unroll
+      for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(&vv[dd][kk]);
+          oacc[d0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kk], oacc[d0 + dd], 0, 0, 0);
+          oacc[d0 + dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo[kk], oacc[d0 + dd], 0, 0, 0);
+        }
+    }
   }
 
   // ---- this split's partial result: lane l holds query row l%32, channels 32 dt + 8 b + 4 h + (0..3)
@@ -423,10 +504,11 @@ void attention_plan(int n_kv, int group, int max_block_tokens, long total_steps,
                     int* max_splits) {
   const int tiles = ceil_div(max_block_tokens * group, 32);
   const int waves = tiles < 8 ? (tiles > 0 ? tiles : 1) : 8;
-  constexpr int kWavesPerCu = 8;     // by registers
+  constexpr int kWavesPerCu = 12;    // by registers (three waves per SIMD)
   const int wgs_per_cu = kWavesPerCu / waves < 5 ? (kWavesPerCu / waves > 0 ? kWavesPerCu / waves : 1) : 5;   // 5 workgroups by LDS
   const long slots = 256L * wgs_per_cu;
-  long sps = (total_steps * n_kv + 4 * slots - 1) / (4 * slots);
+  constexpr int kRounds = 2;
+  long sps = (total_steps * n_kv + kRounds * slots - 1) / (kRounds * slots);
   if (sps < 6) sps = 6;
   const long lo = (max_steps + 31) / 32;                        // at most 32 splits per server
   if (sps < lo) sps = lo;
@@ -444,17 +526,17 @@ size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_split
 
 template <int HD, int G>
 static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf16_t* v_pages, const int* block_table,
-                               int max_blocks, const int* cu_rows, const int* ctx_len, int n_servers, int page_size,
+                               int max_blocks, const int* work, int n_work, int page_size,
                                int n_heads, int n_kv, int max_block_tokens, int steps_per_split, int max_splits,
                                float* po, float* pml, hipStream_t stream) {
   const int tiles = ceil_div(max_block_tokens * G, 32);
-  dim3 grid(max_splits, n_kv, n_servers);
+  dim3 grid(n_work, n_kv);
   for (int t0 = 0; t0 < tiles; t0 += 8) {      // at most 8 query tiles (waves) per workgroup
     const int waves = tiles - t0 < 8 ? tiles - t0 : 8;
 #define GS_RING(NW_)                                                                                              \
-  attn_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, cu_rows,   \
-                                                         ctx_len, page_size, n_heads, n_kv, steps_per_split,      \
-                                                         max_splits, t0 * 32, po, pml)
+  attn_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, work,      \
+                                                         page_size, n_heads, n_kv, steps_per_split, max_splits,   \
+                                                         t0 * 32, po, pml)
     switch (waves) {
       case 1: GS_RING(1); break;
       case 2: GS_RING(2); break;
@@ -471,12 +553,26 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
   return GS_OK;
 }
 
-// attn_out [R][H*hd] (storage type).  scratch: attention_workspace_floats floats (bf16 path only).
+// Number of ints of a work list with room for `capacity` entries.
+size_t attention_work_ints(int capacity) { return 8 + 8 * (size_t)capacity; }
+
+// Builds the step's work list (bf16 path): once per step, the block tables being the same for every layer.
+gs_status launch_attention_work(const int* cu_rows, const int* ctx_len, int n_servers, const int* block_table,
+                                int max_blocks, int page_size, int steps_per_split, int capacity, int* work,
+                                hipStream_t stream) {
+  attn_work_kernel<<<1, 256, 0, stream>>>(cu_rows, ctx_len, n_servers, block_table, max_blocks, page_size,
+                                          steps_per_split, capacity, work);
+  GS_LAUNCH_CHECK("attn_work");
+  return GS_OK;
+}
+
+// attn_out [R][H*hd] (storage type).  scratch: attention_workspace_floats floats; work, n_work: the step's work
+// list and its length as the host computes it from its copy of the batch geometry (bf16 path only).
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
                            int max_block_tokens, int steps_per_split, int max_splits, const void* row_info,
-                           float* scratch, void* attn_out, hipStream_t stream) {
+                           const int* work, int n_work, float* scratch, void* attn_out, hipStream_t stream) {
   if (dtype == GS_F32) {
     dim3 grid(n_rows, n_heads);
     const float* qf = static_cast<const float*>(q);
@@ -501,8 +597,8 @@ gs_status launch_attention(int dtype, const void* q, const void* k_pages, const 
   gs_status st = GS_OK;
 #define GS_ATTN_CASE(HD_, G_)                                                                                     \
   if (hd == HD_ && G == G_)                                                                                       \
-    st = launch_mfma_g<HD_, G_>(qb, kb, vb, block_table, max_blocks, cu_rows, ctx_len, n_servers, page_size,     \
-                                n_heads, n_kv, max_block_tokens, steps_per_split, max_splits, po, pml, stream);
+    st = launch_mfma_g<HD_, G_>(qb, kb, vb, block_table, max_blocks, work, n_work, page_size, n_heads, n_kv,     \
+                                max_block_tokens, steps_per_split, max_splits, po, pml, stream);
   GS_ATTN_CASE(128, 1) GS_ATTN_CASE(128, 2) GS_ATTN_CASE(128, 4) GS_ATTN_CASE(128, 8)
   GS_ATTN_CASE(64, 1) GS_ATTN_CASE(64, 2) GS_ATTN_CASE(64, 4) GS_ATTN_CASE(64, 8)
 #undef GS_ATTN_CASE

@@ -33,8 +33,11 @@ gs_status launch_attention(int dtype, const void* q, const void* k_pages, const 
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
                            int n_servers, int n_rows, int page_size, int n_heads, int n_kv, int hd,
                            int max_block_tokens, int steps_per_split, int max_splits, const void* row_info,
-                           float* scratch, void* attn_out,
-                           hipStream_t stream);
+                           const int* work, int n_work, float* scratch, void* attn_out, hipStream_t stream);
+size_t attention_work_ints(int capacity);
+gs_status launch_attention_work(const int* cu_rows, const int* ctx_len, int n_servers, const int* block_table,
+                                int max_blocks, int page_size, int steps_per_split, int capacity, int* work,
+                                hipStream_t stream);
 gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
                         const float* q_probs, const int* draft_tokens, const float* u_accept,
                         const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream);
@@ -75,6 +78,8 @@ struct Plan {
   int* draft_tokens;
   void* row_slot;   // [R] (page, slot of the row's own K/V, keys of its server, server)
   void* rope;       // [R][hd/2] (cos, sin)
+  int* attn_work;   // the step's (server, split) work list of the attention kernel
+  int attn_work_capacity;
   void* accept_ws;
   size_t bytes;
 };
@@ -115,8 +120,9 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   // the planner never uses more than 32 splits per server and never fewer than 6 steps per split
   const int max_steps = (max_ctx + 31) / 32;
   const int max_splits = std::max(1, std::min(32, (max_steps + 5) / 6)) | 1;   // odd, like the planner's
-  (void)max_servers;
   p.attn_scratch = c.take<float>(gs::attention_workspace_floats(max_rows, m.n_heads, m.head_dim, max_splits));
+  p.attn_work_capacity = max_servers * max_splits;
+  p.attn_work = c.take<int>(gs::attention_work_ints(p.attn_work_capacity));
   p.logits = c.take<float>(R * m.vocab);
   p.draft_tokens = c.take<int>(R);
   p.row_slot = c.take<int>(4 * R);
@@ -350,6 +356,11 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     if (st != GS_OK) return st; \
   } while (0)
 
+  int attn_items = 0;      // (server, split) pairs with keys: the length of the attention work list
+  for (int i = 0; i < n; ++i)
+    attn_items += ((b->ctx_len_host[i] + b->gamma_host[i] + 1 + 31) / 32 + attn_sps - 1) / attn_sps;
+  if (attn_items > p.attn_work_capacity) return gs::fail(GS_ECAPACITY, "attention work list overflow");
+
   StageTimer timer(ctx, stream);
 #define GS_STAGE(stage, call)   \
   do {                          \
@@ -360,6 +371,9 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(act, ctx->embed, b->tokens, p.x, rows, d, stream));
   GS_STAGE(GS_STAGE_GLUE, gs::launch_row_meta(b->cu_rows, b->ctx_len, n, rows, b->block_table, b->max_blocks, kv->page_size,
                                               m.head_dim, m.rope_theta, p.row_slot, p.rope, stream));
+  if (act == GS_BF16)
+    GS_STAGE(GS_STAGE_GLUE, gs::launch_attention_work(b->cu_rows, b->ctx_len, n, b->block_table, b->max_blocks,
+                                                      kv->page_size, attn_sps, p.attn_work_capacity, p.attn_work, stream));
   const float* pending = nullptr;   // split-K partials of the projection whose result is still to be added to x
   int pending_splits = 0;
   for (int l = 0; l < m.n_layers; ++l) {
@@ -374,7 +388,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
                                   p.rope, kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, p.q, kl, vl, stream));
     GS_STAGE(GS_STAGE_ATTENTION, gs::launch_attention(act, p.q, kl, vl, b->block_table, b->max_blocks, b->cu_rows, b->ctx_len, n, rows,
                                 kv->page_size, m.n_heads, m.n_kv_heads, m.head_dim, max_t, attn_sps, attn_splits,
-                                p.row_slot, p.attn_scratch, p.attn, stream));
+                                p.row_slot, p.attn_work, attn_items, p.attn_scratch, p.attn, stream));
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
     GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(act, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
                                                    ctx->norm2[l], m.rms_eps, p.h, d, stream));
