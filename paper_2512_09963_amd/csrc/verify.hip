@@ -26,8 +26,8 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              const void* rope, int page_size, int n_heads, int n_kv, int hd, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream);
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
-void attention_plan(int n_kv, int group, int max_block_tokens, long total_steps, int max_steps, int* steps_per_split,
-                    int* max_splits);
+void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, long total_steps, int max_steps,
+                    int* steps_per_split, int* max_splits);
 size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits);
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
@@ -347,7 +347,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   const int F = m.d_ffn;
   const size_t layer_stride = (size_t)kv->n_pages * m.n_kv_heads * kv->page_size * m.head_dim * ctx->elem;
   int attn_sps = 1, attn_splits = 1;
-  gs::attention_plan(m.n_kv_heads, m.n_heads / m.n_kv_heads, max_t, total_steps, (max_ctx + 31) / 32, &attn_sps,
+  gs::attention_plan(m.n_kv_heads, m.n_heads / m.n_kv_heads, max_t, n, total_steps, (max_ctx + 31) / 32, &attn_sps,
                      &attn_splits);
   gs_status st;
 #define GS_TRY(call)          \
