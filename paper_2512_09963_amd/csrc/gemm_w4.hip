@@ -7,6 +7,7 @@
 // issue rate of the 16x16x32 one on this chip): a wave owns 32 output columns and up to 128 rows and reads,
 // per 64-wide k step, 16 bytes per lane (32 codes of one column) plus one 32-bit word with the column's
 // scale and zero point; the codes are turned into bf16 in registers and fed to the MFMA as the B operand.
+// Beyond 64 rows a wave owns two such column tiles, so that an activation fragment read from LDS feeds two MFMAs.
 // Dequantisation: four codes are spread to the bytes of a word (two mask operations per eight codes), each
 // byte is converted to fp32 by the byte-conversion instruction, fma(c, scale, -zero * scale) = (c - zero) *
 // scale is exact in fp32 (5 x 8 significant bits), and the packed conversion rounds it to bf16 (nearest
@@ -29,7 +30,6 @@ namespace {
 constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;
 constexpr int kGroup = 128;
-constexpr int kDepth = 4;
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 
@@ -38,33 +38,40 @@ struct W4Step {
   uint32_t meta;
 };
 
+// float(byte B of x): the byte-select forms of the conversion, written out because the compiler otherwise
+// extracts each nibble with a bit-field instruction first (two instructions per code instead of one)
+template <int B>
+__device__ __forceinline__ float byte_to_float(uint32_t x) {
+  float f;
+  if constexpr (B == 0) asm("v_cvt_f32_ubyte0_e32 %0, %1" : "=v"(f) : "v"(x));
+  else if constexpr (B == 1) asm("v_cvt_f32_ubyte1_e32 %0, %1" : "=v"(f) : "v"(x));
+  else if constexpr (B == 2) asm("v_cvt_f32_ubyte2_e32 %0, %1" : "=v"(f) : "v"(x));
+  else asm("v_cvt_f32_ubyte3_e32 %0, %1" : "=v"(f) : "v"(x));
+  return f;
+}
+
 // word: codes 0..3 in the even nibbles of bytes 0..3, codes 4..7 in the odd nibbles
 __device__ __forceinline__ bf16x8_t dequant8(uint32_t word, float scale, float neg_zs) {
   const uint32_t lo4 = word & 0x0F0F0F0Fu, hi4 = (word >> 4) & 0x0F0F0F0Fu;
-  float f[8];
-  f[0] = (float)(lo4 & 0xffu);
-  f[1] = (float)((lo4 >> 8) & 0xffu);
-  f[2] = (float)((lo4 >> 16) & 0xffu);
-  f[3] = (float)(lo4 >> 24);
-  f[4] = (float)(hi4 & 0xffu);
-  f[5] = (float)((hi4 >> 8) & 0xffu);
-  f[6] = (float)((hi4 >> 16) & 0xffu);
-  f[7] = (float)(hi4 >> 24);
   uint4 out;
-  out.x = pack_bf16x2(fmaf(f[0], scale, neg_zs), fmaf(f[1], scale, neg_zs));
-  out.y = pack_bf16x2(fmaf(f[2], scale, neg_zs), fmaf(f[3], scale, neg_zs));
-  out.z = pack_bf16x2(fmaf(f[4], scale, neg_zs), fmaf(f[5], scale, neg_zs));
-  out.w = pack_bf16x2(fmaf(f[6], scale, neg_zs), fmaf(f[7], scale, neg_zs));
+  out.x = pack_bf16x2(fmaf(byte_to_float<0>(lo4), scale, neg_zs), fmaf(byte_to_float<1>(lo4), scale, neg_zs));
+  out.y = pack_bf16x2(fmaf(byte_to_float<2>(lo4), scale, neg_zs), fmaf(byte_to_float<3>(lo4), scale, neg_zs));
+  out.z = pack_bf16x2(fmaf(byte_to_float<0>(hi4), scale, neg_zs), fmaf(byte_to_float<1>(hi4), scale, neg_zs));
+  out.w = pack_bf16x2(fmaf(byte_to_float<2>(hi4), scale, neg_zs), fmaf(byte_to_float<3>(hi4), scale, neg_zs));
   return *reinterpret_cast<const bf16x8_t*>(&out);
 }
 
-// MT32 row tiles of 32 rows per workgroup (1, 2 or 4), NW waves of 32 columns each.
-template <int MT32, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restrict__ X,
+// MT32 row tiles of 32 rows per workgroup (1, 2 or 4), NW waves of NT 32-column tiles each.  With one
+// column tile per wave every MFMA needs an activation fragment of its own from LDS (1 KB per 32 MFMA
+// cycles and wave: the LDS limit at four row tiles); with two, a fragment serves two MFMAs.  DX: steps the
+// activation tile is fetched ahead (registers, then LDS); the weights are fetched DW steps ahead.
+template <int MT32, int NW, int NT, int DW, int DX>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(MT32 == 4 && NW >= 4 ? 2 : 1))) void gemm_w4_kernel(const bf16_t* __restrict__ X,
                                                           const uint4* __restrict__ codes,
                                                           const uint32_t* __restrict__ meta,
                                                           float* __restrict__ P, int M, int N, int K,
                                                           int k_per_split, int m_chunks) {
+  static_assert(DW % DX == 0, "the unrolled ring addresses the activation slots statically");
   constexpr int ROWS = MT32 * 32;
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][ROWS * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -74,9 +81,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restri
     const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
     m_chunk = t % m_chunks;
     n_block = (t / m_chunks) * 8 + xcd;
-    if (n_block * (32 * NW) >= N) return;
+    if (n_block * (32 * NW * NT) >= N) return;
   }
-  const int n_tile = n_block * NW + wave;        // 32-column tile
+  const int n_tile = (n_block * NW + wave) * NT;        // first 32-column tile of this wave
   const int n0 = n_tile * 32;
   const int split = blockIdx.y;
   const int m0 = m_chunk * ROWS;
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restri
   constexpr int kThreads = 64 * NW;
   constexpr int kChunks = ROWS * 8;
   constexpr int kPasses = (kChunks + kThreads - 1) / kThreads;
-  uint4 xreg[kDepth][kPasses];
+  uint4 xreg[DX][kPasses];
   auto load_x = [&](int slot, int step) {
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
@@ -111,49 +118,81 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restri
   const size_t code_stride = (size_t)(N / 32) * 64;       // uint4 per k step
   const uint4* cbase = codes + (size_t)step0 * code_stride + (size_t)n_tile * 64 + lane;
   const uint32_t* mbase = meta + n0 + c32;
-  W4Step wreg[kDepth];
+  W4Step wreg[DW][NT];
   auto load_w = [&](int slot, int step) {
-    wreg[slot].codes = cbase[(size_t)step * code_stride];
-    wreg[slot].meta = mbase[(size_t)((step0 + step) >> 1) * N];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      wreg[slot][nt].codes = cbase[(size_t)step * code_stride + nt * 64];
+      wreg[slot][nt].meta = mbase[(size_t)((step0 + step) >> 1) * N + nt * 32];
+    }
   };
 
-  floatx16_t acc[MT32];
+  floatx16_t acc[MT32][NT];
 #pragma unroll
   for (int mt = 0; mt < MT32; ++mt)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[mt][e] = 0.f;
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-  for (int d = 0; d < kDepth; ++d)
+      for (int e = 0; e < 16; ++e) acc[mt][nt][e] = 0.f;
+#pragma unroll
+  for (int d = 0; d < DW; ++d)
     if (d < n_steps) {
       load_w(d, d);
-      load_x(d, d);
+      if (d < DX) load_x(d, d);
     }
   // A fragment of row tile mt, k group kg: row mt*32 + lane%32, 16-byte piece 2 kg + lane/32
   const int a_lane = c32 * kLdsRow + h * 8;
-  for (int base = 0; base < n_steps; base += kDepth) {
+  auto dequant_group = [&](const W4Step (&w)[NT], int kg, bf16x8_t (&b)[NT]) {
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
+    for (int nt = 0; nt < NT; ++nt) {
+      const float scale = __uint_as_float(w[nt].meta & 0xffff0000u);
+      const float neg_zs = -(float)(w[nt].meta & 0xffu) * scale;
+      const uint32_t cw = kg == 0 ? w[nt].codes.x : kg == 1 ? w[nt].codes.y : kg == 2 ? w[nt].codes.z : w[nt].codes.w;
+      b[nt] = dequant8(cw, scale, neg_zs);
+    }
+  };
+  // Software pipeline: the activation fragments (LDS) and the dequantised weights (vector ALU) of k group
+  // kg + 1 are produced while the MFMAs of group kg run; the weights of a step's first group are dequantised
+  // during the last group of the step before, since they do not wait for the barrier.
+  bf16x8_t b_cur[NT];
+  if (n_steps > 0) dequant_group(wreg[0], 0, b_cur);
+  for (int base = 0; base < n_steps; base += DW) {
+#pragma unroll
+    for (int d = 0; d < DW; ++d) {
       const int step = base + d;
       if (step < n_steps) {
         const int buf = step & 1;
-        store_x(buf, d);
+        store_x(buf, d % DX);
         __syncthreads();
-        const W4Step w = wreg[d];
-        if (step + kDepth < n_steps) {
-          load_w(d, step + kDepth);
-          load_x(d, step + kDepth);
-        }
-        const float scale = __uint_as_float(w.meta & 0xffff0000u);
-        const float neg_zs = -(float)(w.meta & 0xffu) * scale;
-        const uint32_t cw[4] = {w.codes.x, w.codes.y, w.codes.z, w.codes.w};
+        W4Step w[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) w[nt] = wreg[d][nt];
+        if (step + DW < n_steps) load_w(d, step + DW);
+        if (step + DX < n_steps) load_x(d % DX, step + DX);
+        bf16x8_t a_cur[MT32];
+#pragma unroll
+        for (int mt = 0; mt < MT32; ++mt)
+          a_cur[mt] = *reinterpret_cast<const bf16x8_t*>(&xs[buf][mt * 32 * kLdsRow + a_lane]);
 #pragma unroll
         for (int kg = 0; kg < 4; ++kg) {
-          const bf16x8_t b = dequant8(cw[kg], scale, neg_zs);
+          bf16x8_t a_nxt[MT32], b_nxt[NT];
+          if (kg < 3) {
 #pragma unroll
-          for (int mt = 0; mt < MT32; ++mt) {
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&xs[buf][mt * 32 * kLdsRow + a_lane + kg * 16]);
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
+            for (int mt = 0; mt < MT32; ++mt)
+              a_nxt[mt] = *reinterpret_cast<const bf16x8_t*>(&xs[buf][mt * 32 * kLdsRow + a_lane + (kg + 1) * 16]);
+            dequant_group(w, kg + 1, b_nxt);
+          } else if (step + 1 < n_steps) {
+            dequant_group(wreg[(d + 1) % DW], 0, b_nxt);
           }
+#pragma unroll
+          for (int mt = 0; mt < MT32; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[mt], b_cur[nt], acc[mt][nt], 0, 0, 0);
+#pragma unroll
+          for (int mt = 0; mt < MT32; ++mt) a_cur[mt] = a_nxt[mt];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) b_cur[nt] = b_nxt[nt];
         }
       }
     }
@@ -164,7 +203,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_w4_kernel(const bf16_t* __restri
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int row = m0 + mt * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-      if (row < M) out[(size_t)row * N + n0 + c32] = acc[mt][v];
+      if (row < M) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) out[(size_t)row * N + n0 + nt * 32 + c32] = acc[mt][nt][v];
+      }
     }
 }
 
@@ -214,18 +256,30 @@ gs_status launch_pack_weight_w4(const void* q, const void* scales, const void* z
   return GS_OK;
 }
 
-// Launch shape of the 4-bit kernel: 32-row tiles per workgroup (1, 2 or 4), row chunks of 128, waves, K splits.
+// Launch shape of the 4-bit kernel: 32-row tiles per workgroup (1, 2 or 4), row chunks of 128, waves, column
+// tiles per wave, K splits.
 struct W4Plan {
-  int mt32, m_chunks, waves, splits, k_per;
+  int mt32, m_chunks, waves, nt, splits, k_per;
 };
 
 static W4Plan w4_plan(int M, int N, int K) {
   W4Plan p;
   p.mt32 = M <= 32 ? 1 : M <= 64 ? 2 : 4;
   p.m_chunks = ceil_div(M, 32 * p.mt32);
-  p.waves = (N % 256 == 0 && N / 256 >= 96) ? 8 : (N % 128 == 0 ? 4 : 2);
-  const int wgs = N / (32 * p.waves) * p.m_chunks;
-  int want = (512 + wgs / 2) / wgs;
+  p.nt = 1;
+  if (p.mt32 == 4 && N % 512 == 0 && N / 512 >= 96) {
+    p.waves = 8; p.nt = 2;
+  } else if (p.mt32 == 4 && N % 256 == 0) {
+    p.waves = 4; p.nt = 2;
+  } else {
+    p.waves = (N % 256 == 0 && N / 256 >= 96) ? 8 : (N % 128 == 0 ? 4 : 2);
+  }
+  const int wgs = N / (32 * p.waves * p.nt) * p.m_chunks;
+  // K splits: enough workgroups to stream from every CU while the weights are the bound (512); one workgroup
+  // per CU at four row tiles, where the MFMA work is the bound and every further split only adds an
+  // M x N fp32 partial result to write and re-read (measured on the 70B shape: 68 instead of 77 us per launch)
+  const int target = p.mt32 == 4 ? 256 : 512;
+  int want = (target + wgs / 2) / wgs;
   const int max_s = K / 512 > 0 ? K / 512 : 1;
   int s = want < max_s ? want : max_s;
   if (s < 1) s = 1;
@@ -239,15 +293,17 @@ int gemm_w4_splits(int M, int N, int K) { return M <= 0 ? 1 : w4_plan(M, N, K).s
 template <int NW>
 static void launch_w4(const W4Plan& p, const bf16_t* x, const uint4* codes, const uint32_t* meta, float* P, int M,
                       int N, int K, hipStream_t stream) {
-  const int n_blocks = N / (32 * NW);
+  const int n_blocks = N / (32 * NW * p.nt);
   const int gx = p.m_chunks > 1 ? ceil_div(n_blocks, 8) * 8 * p.m_chunks : n_blocks;
   const dim3 grid(gx, p.splits, 1);
   if (p.mt32 == 1)
-    gemm_w4_kernel<1, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+    gemm_w4_kernel<1, NW, 1, 4, 4><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
   else if (p.mt32 == 2)
-    gemm_w4_kernel<2, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+    gemm_w4_kernel<2, NW, 1, 4, 4><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+  else if (p.nt == 1)
+    gemm_w4_kernel<4, NW, 1, 4, 4><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
   else
-    gemm_w4_kernel<4, NW><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
+    gemm_w4_kernel<4, NW, 2, 2, (NW >= 8 ? 2 : 1)><<<grid, 64 * NW, 0, stream>>>(x, codes, meta, P, M, N, K, p.k_per, p.m_chunks);
 }
 
 // P [splits][M][N] fp32 partial sums of X [M][K] (bf16) * W^T with W given in the packed 4-bit layout.

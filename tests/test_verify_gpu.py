@@ -189,6 +189,17 @@ def test_bf16_attention_tile_and_split_boundaries(group, gamma, ctx):
     _run_case(ms, 84, np.array(gamma, np.int32), np.array(ctx, np.int32), 16, std=0.08)
 
 
+def test_bf16_more_servers_than_one_round_of_the_attention_work_list():
+    # 300 servers (the work list is built 256 servers at a time), most with a single short split, a few long
+    # enough for several; gamma 0..2, so that the row count stays small for the oracle
+    ms = synth.ModelShape(1, 128, 4, 2, 64, 128, 512, 10000.0, dtype="bf16")
+    rng = np.random.default_rng(85)
+    gamma = rng.integers(0, 3, 300).astype(np.int32)
+    ctx = rng.integers(0, 40, 300).astype(np.int32)
+    ctx[[3, 130, 255, 256, 299]] = [900, 1500, 700, 2100, 1200]
+    _run_case(ms, 85, gamma, ctx, 16, std=0.08)
+
+
 def test_bf16_page_size_48_not_a_power_of_two():
     ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
