@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA path.  grid (max_splits, H_kv, N), NW waves per workgroup.
+// bf16 MFMA path.  grid (work list entries, H_kv), NW waves per workgroup.
 //
 // A workgroup owns steps [split * steps_per_split, ...) of one (server, KV head); a step is 32
 // keys = two 16-key tiles = 16 KB of K and V at hd 128.  K/V go from global memory straight into
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 // parts, K and V of either tile; part p is loaded by wave p % NW (waves 0..3 when NW > 4), whose
 // HD/32 load instructions of 1 KB each share one scalar base address.  One barrier per step both
 // publishes the stage that has landed and frees the stage that is refilled next.  (Deeper buffers
-// were measured and are slower.)  K is placed in LDS so that lane (g, c) of fragment (tile, ks) holds
+// were measured, with and without the arithmetic: no gain.)  K is placed in LDS so that lane (g, c) of fragment (tile, ks) holds
 // key c, channels 32 ks + 8 g .. at fragment * 1 KB + lane * 16; V pages are copied verbatim
 // ([channel][16 slots] per tile).
 // Wave w computes query rows 32 w .. 32 w + 31 of the T_i * G rows that share the KV head (token-major,
