@@ -158,8 +158,8 @@ def accept_leg(seed):
 
 
 def cpu_baseline(ms, w, seed):
-    """The oracle as it stands on the host cores: embed + 1 and 2 decoder layers + LM head + accept,
-    extrapolated linearly in the layer count to the full depth."""
+    """The oracle as it stands on the host cores: embedding + 8 and 16 decoder layers + LM head, and the accept
+    stage in full (about 10 s of host work), extrapolated linearly in the layer count to the full depth."""
     import dataclasses
     from oracle import accept_reject as ar, forward as fw
     from paper_2512_09963_amd import synth
@@ -170,7 +170,7 @@ def cpu_baseline(ms, w, seed):
         cores = len(os.sched_getaffinity(0))
     batch = w["batch"]
     times = {}
-    n_sample = 8      # decoder layers timed; enough for some tens of seconds of host work
+    n_sample = 16     # decoder layers timed: about 10 s of host work
     layers = [synth.layer_weights(ms, seed, l) for l in range(n_sample)]
     top = synth.top_weights(ms, seed)
     logits = None
