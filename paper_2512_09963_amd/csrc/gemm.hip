@@ -145,6 +145,102 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
   }
 }
 
+// Gate/up projection with the SwiGLU in its epilogue (up to 64 rows): act[r][f] = silu(X W_gate^T) * (X W_up^T)
+// with W = [gate rows; up rows] ([2F][K], packed).  A wave owns feature tile t of both halves (column tiles
+// t and F/16 + t of the packed matrix), so the gate and the up value of an output sit in the same register
+// of the same lane; K is not split, so the sums are complete when the loop ends and the fp32 partial result
+// ([splits][R][2F], written and read back by a separate kernel otherwise) never exists.  grid F / (16 NW).
+template <int MT, int DEPTH, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_gate_up_kernel(const bf16_t* __restrict__ X,
+                                                                    const bf16_t* __restrict__ Wp,
+                                                                    bf16_t* __restrict__ act, int M, int F, int K) {
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const int f_tile = blockIdx.x * NW + wave;
+  const int n_steps = K / kBK;
+
+  constexpr int kChunks = MT * 128;
+  constexpr int kGemmThreads = 64 * NW;
+  constexpr int kPasses = (kChunks + kGemmThreads - 1) / kGemmThreads;
+  uint4 xreg[DEPTH][kPasses];
+  auto load_x = [&](int slot, int step) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * kGemmThreads;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ch < kChunks && row < M) v = *reinterpret_cast<const uint4*>(X + (size_t)row * K + step * kBK + col);
+      xreg[slot][p] = v;
+    }
+  };
+  auto store_x = [&](int buf, int slot) {
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int ch = tid + p * kGemmThreads;
+      const int row = ch >> 3, col = (ch & 7) * 8;
+      if (ch < kChunks) *reinterpret_cast<uint4*>(&xs[buf][row * kLdsRow + col]) = xreg[slot][p];
+    }
+  };
+  const size_t w_step_stride = (size_t)(2 * F / 16) * 128;
+  const uint4* wgate = reinterpret_cast<const uint4*>(Wp) + (size_t)f_tile * 128 + lane;
+  const uint4* wup = wgate + (size_t)(F / 16) * 128;
+  uint4 wreg[DEPTH][2][2];
+  auto load_w = [&](int slot, int step) {
+    const size_t o = (size_t)step * w_step_stride;
+    wreg[slot][0][0] = wgate[o];
+    wreg[slot][0][1] = wgate[o + 64];
+    wreg[slot][1][0] = wup[o];
+    wreg[slot][1][1] = wup[o + 64];
+  };
+  floatx4_t acc_g[MT], acc_u[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc_g[mt] = acc_u[mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < n_steps) {
+      load_w(d, d);
+      load_x(d, d);
+    }
+  for (int base = 0; base < n_steps; base += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int step = base + d;
+      if (step < n_steps) {
+        const int buf = step & 1;
+        store_x(buf, d);
+        __syncthreads();
+        const uint4 g0 = wreg[d][0][0], g1 = wreg[d][0][1], u0 = wreg[d][1][0], u1 = wreg[d][1][1];
+        if (step + DEPTH < n_steps) {
+          load_w(d, step + DEPTH);
+          load_x(d, step + DEPTH);
+        }
+        const bf16x8_t bg0 = *reinterpret_cast<const bf16x8_t*>(&g0), bg1 = *reinterpret_cast<const bf16x8_t*>(&g1);
+        const bf16x8_t bu0 = *reinterpret_cast<const bf16x8_t*>(&u0), bu1 = *reinterpret_cast<const bf16x8_t*>(&u1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const bf16_t* ap = &xs[buf][(mt * 16 + c) * kLdsRow + g * 16];
+          const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(ap);
+          const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(ap + 8);
+          acc_g[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bg0, acc_g[mt], 0, 0, 0);
+          acc_u[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bu0, acc_u[mt], 0, 0, 0);
+          acc_g[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bg1, acc_g[mt], 0, 0, 0);
+          acc_u[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bu1, acc_u[mt], 0, 0, 0);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = mt * 16 + g * 4 + i;
+      const float gt = acc_g[mt][i];
+      if (row < M) act[(size_t)row * F + f_tile * 16 + c] = float_to_bf16(gt / (1.0f + expf(-gt)) * acc_u[mt][i]);
+    }
+  }
+}
+
 // More than 64 rows (a few hundred per step with tens of draft servers): the same streaming design
 // with a taller and wider wave tile.  A wave owns NT column tiles and all MT * 16 rows of its row
 // chunk, so every activation fragment read from LDS feeds NT MFMAs and every weight fragment MT of
@@ -156,11 +252,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
 // handed to the 8 XCDs round robin by their linear index, so the chunks of a column block get indices
 // that are 8 apart and land on the same XCD one after the other, and all but the first find the weights
 // in that XCD's L2.  grid (ceil(N / (64 NT) / 8) * 8 * m_chunks, S).
-template <int MT, int NT, int DEPTH>
+// GATE_UP (NT = 2, one K split): the wave's two column tiles are feature tile t of the gate half and of the
+// up half of a [2F][K] matrix, and the epilogue stores act[r][f] = silu(gate) * up as bf16 ([M][N/2], at P)
+// instead of the fp32 sums.
+template <int MT, int NT, int DEPTH, bool GATE_UP = false>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __restrict__ X,
                                                                 const bf16_t* __restrict__ Wp,
                                                                 float* __restrict__ P, int M, int N, int K,
                                                                 int k_per_split, int m_chunks) {
+  static_assert(!GATE_UP || NT == 2, "gate and up tile of a feature tile");
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
@@ -168,7 +268,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
   const int m_chunk = t % m_chunks;
   const int n_block = (t / m_chunks) * 8 + xcd;
   if (n_block * (64 * NT) >= N) return;        // padding of the grid to a multiple of 8 column blocks
-  const int n_tile0 = (n_block * 4 + wave) * NT;
+  // first column tile of the wave and the distance (in tiles) to its next one
+  const int n_tile0 = GATE_UP ? n_block * 4 + wave : (n_block * 4 + wave) * NT;
+  const int tile_step = GATE_UP ? N / 32 : 1;
   const int split = blockIdx.y;
   const int m0 = m_chunk * (MT * 16);
   const int k_begin = split * k_per_split;
@@ -204,8 +306,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
     const uint4* p = wbase + (size_t)step * w_step_stride;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      wreg[slot][nt][0] = p[nt * 128];
-      wreg[slot][nt][1] = p[nt * 128 + 64];
+      wreg[slot][nt][0] = p[(size_t)nt * tile_step * 128];
+      wreg[slot][nt][1] = p[(size_t)nt * tile_step * 128 + 64];
     }
   };
 
@@ -251,6 +353,19 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
     }
   }
 
+  if constexpr (GATE_UP) {
+    bf16_t* act = reinterpret_cast<bf16_t*>(P);
+    const int F = N / 2;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = m0 + mt * 16 + g * 4 + i;
+        const float gt = acc[mt][0][i];
+        if (row < M) act[(size_t)row * F + n_tile0 * 16 + c] = float_to_bf16(gt / (1.0f + expf(-gt)) * acc[mt][NT - 1][i]);
+      }
+    return;
+  }
   float* out = P + (size_t)split * M * N;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -417,6 +532,49 @@ static void launch_tall(const GemmPlan& p, const bf16_t* x, const bf16_t* w, flo
     case 8: gemm_bf16_tall_kernel<8, 2, 2><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks); break;
     default: gemm_bf16_tall_kernel<10, 2, 2><<<grid, 256, 0, stream>>>(x, w, P, M, N, K, p.k_per, p.m_chunks);
   }
+}
+
+// Gate/up with the SwiGLU fused: 4 waves (64 features per workgroup; 224 workgroups for F = 14336, each wave
+// streaming 256 KB without a K split), weights fetched 6 steps ahead (with 4 the unsplit kernel is 4.5 us
+// slower than the split one on the 8B shape, with 6 it is 1.3 us slower and the 6 us of the separate SwiGLU
+// kernel and its launch boundary are gone; 2 waves double the activation re-reads, 8 leave half the CUs idle).
+constexpr int kGateUpWaves = 4;
+constexpr int kGateUpDepth = 6;
+
+// Whether the gate/up projection of this shape runs with the SwiGLU fused: bf16, and either up to 64 rows or
+// a shape that the tall kernel serves without a K split anyway.
+bool gate_up_fused(int dtype, int M, int F, int K) {
+  if (dtype != GS_BF16 || M <= 0 || F % (16 * kGateUpWaves) != 0 || K % kBK != 0) return false;
+  if (M <= 64) return true;
+  const GemmPlan p = gemm_plan(M, 2 * F, K);
+  return p.tall && p.nt == 2 && p.splits == 1;
+}
+
+// act [M][F] (bf16) = silu(X Wg^T) * (X Wu^T), W = [Wg; Wu] packed; only for shapes gate_up_fused accepts.
+gs_status launch_gemm_gate_up(const void* X, const void* W, void* act, int M, int F, int K, hipStream_t stream) {
+  constexpr int NW = kGateUpWaves, D = kGateUpDepth;
+  const bf16_t* x = static_cast<const bf16_t*>(X);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  bf16_t* a = static_cast<bf16_t*>(act);
+  const int tiles = ceil_div(M, 16);
+  if (tiles > 4) {      // tall kernel, one K split, gate and up tile per wave
+    const GemmPlan p = gemm_plan(M, 2 * F, K);
+    const dim3 grid(ceil_div(2 * F / 128, 8) * 8 * p.m_chunks, 1, 1);
+    float* out = static_cast<float*>(act);
+    switch (p.mt) {
+      case 6: gemm_bf16_tall_kernel<6, 2, 2, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks); break;
+      case 8: gemm_bf16_tall_kernel<8, 2, 2, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks); break;
+      default: gemm_bf16_tall_kernel<10, 2, 2, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks);
+    }
+    GS_LAUNCH_CHECK("gemm_gate_up_tall");
+    return GS_OK;
+  }
+  const int grid = F / (16 * NW);
+  if (tiles <= 1) gemm_bf16_gate_up_kernel<1, D, NW><<<grid, 64 * NW, 0, stream>>>(x, w, a, M, F, K);
+  else if (tiles <= 2) gemm_bf16_gate_up_kernel<2, D, NW><<<grid, 64 * NW, 0, stream>>>(x, w, a, M, F, K);
+  else gemm_bf16_gate_up_kernel<4, D, NW><<<grid, 64 * NW, 0, stream>>>(x, w, a, M, F, K);
+  GS_LAUNCH_CHECK("gemm_gate_up");
+  return GS_OK;
 }
 
 // P [splits][M][N] fp32 partial sums of X [M][K] * W[N][K]^T (W tile-packed for bf16, packed 4-bit for

@@ -16,6 +16,8 @@ size_t w4_packed_bytes(int N, int K);
 gs_status launch_pack_weight_w4(const void* q, const void* scales, const void* zeros, void* packed, int N, int K,
                                 hipStream_t stream);
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream);
+bool gate_up_fused(int dtype, int M, int F, int K);
+gs_status launch_gemm_gate_up(const void* X, const void* W, void* act, int M, int F, int K, hipStream_t stream);
 gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
                              float eps, void* h, int d, hipStream_t stream);
@@ -392,8 +394,12 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.attn, ctx->wo[l], p.partial, rows, d, hq, stream));
     GS_STAGE(GS_STAGE_GLUE, gs::launch_add_rmsnorm(act, p.x, p.partial, gs::gemm_splits(m.dtype, rows, d, hq), rows,
                                                    ctx->norm2[l], m.rms_eps, p.h, d, stream));
-    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
-    GS_STAGE(GS_STAGE_GLUE, gs::launch_swiglu(act, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
+    if (gs::gate_up_fused(m.dtype, rows, F, d)) {
+      GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm_gate_up(p.h, ctx->wgu[l], p.act, rows, F, d, stream));
+    } else {
+      GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->wgu[l], p.partial, rows, 2 * F, d, stream));
+      GS_STAGE(GS_STAGE_GLUE, gs::launch_swiglu(act, p.partial, gs::gemm_splits(m.dtype, rows, 2 * F, d), rows, F, p.act, stream));
+    }
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.act, ctx->wd[l], p.partial, rows, d, F, stream));
     pending = p.partial;
     pending_splits = gs::gemm_splits(m.dtype, rows, d, F);
