@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
                                                                 const bf16_t* __restrict__ Wp,
                                                                 float* __restrict__ P, int M, int N, int K,
                                                                 int k_per_split, int m_chunks) {
-  static_assert(!GATE_UP || NT == 2, "gate and up tile of a feature tile");
+  static_assert(!GATE_UP || NT % 2 == 0, "gate and up tile of every feature tile");
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
@@ -268,9 +268,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
   const int m_chunk = t % m_chunks;
   const int n_block = (t / m_chunks) * 8 + xcd;
   if (n_block * (64 * NT) >= N) return;        // padding of the grid to a multiple of 8 column blocks
-  // first column tile of the wave and the distance (in tiles) to its next one
-  const int n_tile0 = GATE_UP ? n_block * 4 + wave : (n_block * 4 + wave) * NT;
-  const int tile_step = GATE_UP ? N / 32 : 1;
+  // first column tile of the wave; with GATE_UP its tiles are NT/2 neighbouring feature tiles of the gate
+  // half followed by the same ones of the up half (N/32 tiles further)
+  const int n_tile0 = GATE_UP ? (n_block * 4 + wave) * (NT / 2) : (n_block * 4 + wave) * NT;
+  auto tile_offset = [&](int nt) { return GATE_UP ? (nt % (NT / 2)) + (nt / (NT / 2)) * (N / 32) : nt; };
   const int split = blockIdx.y;
   const int m0 = m_chunk * (MT * 16);
   const int k_begin = split * k_per_split;
@@ -306,8 +307,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
     const uint4* p = wbase + (size_t)step * w_step_stride;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      wreg[slot][nt][0] = p[(size_t)nt * tile_step * 128];
-      wreg[slot][nt][1] = p[(size_t)nt * tile_step * 128 + 64];
+      wreg[slot][nt][0] = p[(size_t)tile_offset(nt) * 128];
+      wreg[slot][nt][1] = p[(size_t)tile_offset(nt) * 128 + 64];
     }
   };
 
@@ -361,8 +362,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = m0 + mt * 16 + g * 4 + i;
-        const float gt = acc[mt][0][i];
-        if (row < M) act[(size_t)row * F + n_tile0 * 16 + c] = float_to_bf16(gt / (1.0f + expf(-gt)) * acc[mt][NT - 1][i]);
+        if (row < M) {
+#pragma unroll
+          for (int ft = 0; ft < NT / 2; ++ft) {
+            const float gt = acc[mt][ft][i];
+            act[(size_t)row * F + (n_tile0 + ft) * 16 + c] = float_to_bf16(gt / (1.0f + expf(-gt)) * acc[mt][NT / 2 + ft][i]);
+          }
+        }
       }
     return;
   }
@@ -547,7 +553,7 @@ bool gate_up_fused(int dtype, int M, int F, int K) {
   if (dtype != GS_BF16 || M <= 0 || F % (16 * kGateUpWaves) != 0 || K % kBK != 0) return false;
   if (M <= 64) return true;
   const GemmPlan p = gemm_plan(M, 2 * F, K);
-  return p.tall && p.nt == 2 && p.splits == 1;
+  return p.tall && p.splits == 1;
 }
 
 // act [M][F] (bf16) = silu(X Wg^T) * (X Wu^T), W = [Wg; Wu] packed; only for shapes gate_up_fused accepts.
@@ -559,8 +565,13 @@ gs_status launch_gemm_gate_up(const void* X, const void* W, void* act, int M, in
   const int tiles = ceil_div(M, 16);
   if (tiles > 4) {      // tall kernel, one K split, gate and up tile per wave
     const GemmPlan p = gemm_plan(M, 2 * F, K);
-    const dim3 grid(ceil_div(2 * F / 128, 8) * 8 * p.m_chunks, 1, 1);
+    const dim3 grid(ceil_div(2 * F / (64 * p.nt), 8) * 8 * p.m_chunks, 1, 1);
     float* out = static_cast<float*>(act);
+    if (p.nt == 4) {
+      gemm_bf16_tall_kernel<8, 4, 1, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks);
+      GS_LAUNCH_CHECK("gemm_gate_up_tall");
+      return GS_OK;
+    }
     switch (p.mt) {
       case 6: gemm_bf16_tall_kernel<6, 2, 2, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks); break;
       case 8: gemm_bf16_tall_kernel<8, 2, 2, true><<<grid, 256, 0, stream>>>(x, w, out, M, 2 * F, K, K, p.m_chunks); break;
