@@ -26,8 +26,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "cff0ba9a26cf446542b1ae3a28a8805880b49e2e3ef9f9cb339ccec225403077",
-                "bytes_per_launch": 127128934}
+GEMM_TRAFFIC = {"gemm_hip_sha256": "80d8c04ff8daf99e44db1ff99ff4525d7efd91603a429a97ebb1d863bc038f6a",
+                "bytes_per_launch": 127130057}
 
 
 def measured_traffic():
