@@ -200,6 +200,26 @@ def test_bf16_more_servers_than_one_round_of_the_attention_work_list():
     _run_case(ms, 85, gamma, ctx, 16, std=0.08)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_bf16_seeded_random_shapes(seed):
+    # model widths, head layout, page size, server count, draft lengths and contexts drawn from the seed: walks the
+    # launch planners (row-tile variants of the projections, waves per attention workgroup, split counts)
+    rng = np.random.default_rng(9000 + seed)
+    hd = int(rng.choice([64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    d = 64 * int(rng.integers(2, 6))
+    F = 64 * int(rng.integers(2, 9))
+    V = 64 * int(rng.integers(8, 24))
+    ms = synth.ModelShape(int(rng.integers(1, 3)), d, n_kv * group, n_kv, hd, F, V, 10000.0, dtype="bf16")
+    n = int(rng.integers(1, 12))
+    gamma = rng.integers(0, int(rng.choice([3, 9, 17])), n).astype(np.int32)
+    ctx = rng.integers(0, int(rng.choice([40, 400, 1500])), n).astype(np.int32)
+    page = int(rng.choice([16, 32, 48, 64]))
+    r = _run_case(ms, 9000 + seed, gamma, ctx, page, std=0.08)
+    print(seed, ms, "servers", n, "rows", int(gamma.sum()) + n, "page", page, "worst", r["worst"], r["bands"])
+
+
 def test_bf16_page_size_48_not_a_power_of_two():
     ms = synth.ModelShape(1, 256, 8, 2, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 80, np.array([5, 2, 9], np.int32), np.array([100, 47, 530], np.int32), 48, std=0.08)
