@@ -80,6 +80,12 @@ def test_w4_wide_matrices_use_eight_waves():
     _run(ms, 96, np.array([4, 2], np.int32), np.array([10, 40], np.int32), std=0.05)
 
 
+def test_w4_wide_matrices_with_more_than_64_rows():
+    # 68 rows and N / 512 >= 96 for gate/up (2F = 49152) and the LM head: 8 waves with two column tiles each
+    ms = synth.ModelShape(1, 128, 2, 1, 64, 24576, 49152, 10000.0, dtype="bf16")
+    _run(ms, 97, np.array([16, 16, 16, 16], np.int32), np.array([10, 40, 0, 77], np.int32), std=0.05)
+
+
 def test_w4_shapes_are_validated():
     import torch
     from paper_2512_09963_amd import binding as gsb
