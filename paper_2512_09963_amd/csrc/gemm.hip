@@ -15,7 +15,9 @@
 //     in LDS (padded rows: conflict-free 16-byte reads) and shared by the four waves; their
 //     global loads run DEPTH steps ahead as well, so a step never waits on the L2 round trip
 //   * K is split across workgroups when N alone gives too few of them to fill 256 CUs; the
-//     fp32 partial sums [S][M][N] are summed by the consumer kernel, in a fixed order.
+//     fp32 partial sums [S][M][N] are summed by the consumer kernel, in a fixed order
+//   * the gate/up projection, where it runs without a K split, applies the SwiGLU in its epilogue and
+//     stores the bf16 activation instead of fp32 sums (gemm_bf16_gate_up_kernel, GATE_UP of the tall kernel).
 // k order inside a step is permuted identically for both operands (lane group g takes
 // k = 16g .. 16g+15, first half to the first MFMA, second half to the second), which leaves
 // the dot products unchanged.  Measured without the activation side, on the gate/up shape: 6.2 TB/s
