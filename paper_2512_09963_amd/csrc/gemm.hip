@@ -30,6 +30,14 @@
 namespace gs {
 namespace {
 
+// 16-byte load that does not displace cache lines: weights that a launch reads once (measured on the 8B shape
+// at 50 rows: 4.52 instead of 4.56 ms per step)
+typedef unsigned int uint4_vec __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load(const uint4* p) {
+  const uint4_vec v = __builtin_nontemporal_load(reinterpret_cast<const uint4_vec*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 constexpr int kSkinnyDepth = 4;     // k steps of weights and activations in flight per wave
 constexpr int kTargetWorkgroups = 512;   // about two per CU
 constexpr int kBK = 64;           // k elements per step
@@ -94,8 +102,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
   uint4 wreg[DEPTH][2];
   auto load_w = [&](int slot, int step) {
     const uint4* p = wbase + (size_t)step * w_step_stride;
-    wreg[slot][0] = p[0];
-    wreg[slot][1] = p[64];
+    if (m_chunks == 1) {      // read once: do not displace the activations and partial sums in L2
+      wreg[slot][0] = stream_load(p);
+      wreg[slot][1] = stream_load(p + 64);
+    } else {                  // the other row chunks of the column block read the same weights from L2
+      wreg[slot][0] = p[0];
+      wreg[slot][1] = p[64];
+    }
   };
 
   floatx4_t acc[MT];
@@ -190,10 +203,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_gate_up_kernel(const bf16_t
   uint4 wreg[DEPTH][2][2];
   auto load_w = [&](int slot, int step) {
     const size_t o = (size_t)step * w_step_stride;
-    wreg[slot][0][0] = wgate[o];
-    wreg[slot][0][1] = wgate[o + 64];
-    wreg[slot][1][0] = wup[o];
-    wreg[slot][1][1] = wup[o + 64];
+    wreg[slot][0][0] = stream_load(wgate + o);
+    wreg[slot][0][1] = stream_load(wgate + o + 64);
+    wreg[slot][1][0] = stream_load(wup + o);
+    wreg[slot][1][1] = stream_load(wup + o + 64);
   };
   floatx4_t acc_g[MT], acc_u[MT];
 #pragma unroll
