@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 # profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
 GEMM_TRAFFIC = {"gemm_hip_sha256": "e95585e275602f49bb6b8a7cce30ebe7f6daff6f5b4fc6721624f02eb0a1f807",
-                "bytes_per_launch": 127129129}
+                "bytes_per_launch": 127129895}
 
 
 def measured_traffic():
