@@ -86,3 +86,18 @@ def test_accept_reject_validates_on_the_host_before_any_launch():
     g[1] = 2
     rc = L.gs_accept_reject(2, g.ctypes.data, 8, 16, 8, 8, 8, 8, 8, C.byref(out), 8, 16, None)
     assert rc == -3
+
+
+def test_baseline_allocation_policies_of_the_loop_equal_the_oracle():
+    """Host logic of the closed loop: the even and the random split (no GPU involved)."""
+    from oracle import closed_loop as ol
+    from paper_2512_09963_amd import closed_loop as cl
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        n = int(rng.integers(1, 12))
+        C = int(rng.integers(0, 60))
+        np.testing.assert_array_equal(cl.even_split(C, n), ol.fixed_allocation(C, n))
+        u = rng.random(C + 3).astype(np.float32)
+        got = cl.random_split(C, n, u)
+        np.testing.assert_array_equal(got, ol.random_allocation(C, n, u))
+        assert got.sum() == C
