@@ -86,6 +86,22 @@ def test_w4_wide_matrices_with_more_than_64_rows():
     _run(ms, 97, np.array([16, 16, 16, 16], np.int32), np.array([10, 40, 0, 77], np.int32), std=0.05)
 
 
+def test_w4_real_8b_widths():
+    """The widths bench.py times with 4-bit weights: d 4096, QKV 6144, FFN 14336, vocab 128256, K up to 14336
+    with its K splits; two layers, the 50 rows and 2048-token contexts of the headline configuration."""
+    ms = dataclasses.replace(synth.LLAMA3_8B, n_layers=2)
+    gamma = synth.uniform_int(synth.MASTER_SEED, ("cfg3", "gamma"), 3, 8, 8)
+    _run(ms, 98, gamma, np.full(8, 2048, np.int32), std=0.02)
+
+
+def test_w4_real_70b_widths():
+    """d 8192, QKV 10240, FFN 28672 (K up to 28672), vocab 128256; one layer, 98 rows (the kernel shape with two
+    column tiles per wave), 4096-token contexts."""
+    ms = dataclasses.replace(synth.LLAMA3_70B, n_layers=1)
+    gamma = synth.uniform_int(synth.MASTER_SEED, ("cfg5", "gamma"), 2, 8, 16)
+    _run(ms, 99, gamma, np.full(16, 4096, np.int32), std=0.02)
+
+
 def test_w4_shapes_are_validated():
     import torch
     from paper_2512_09963_amd import binding as gsb
