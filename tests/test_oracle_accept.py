@@ -270,3 +270,30 @@ def test_resample_band_contains_the_oracle_token():
         tok = ar.inverse_cdf(ar.residual_weights(ar.softmax(tl), q), u)
         lo, hi = ar.resample_band(tl, q, u)
         assert lo <= tok <= hi and hi - lo <= 1
+
+
+def test_resample_band_is_no_wider_than_the_rounding_it_excuses():
+    """Hand-built CDF with edges at 1/4 and 1/2 (p = [1/4, 1/4, 1/2], bonus draw): away from an edge the band is
+    the oracle's token alone; within 1e-5 of an edge it is exactly the two tokens that meet there; just
+    outside 1e-5 it is one token again.  A band that is too generous anywhere fails here."""
+    tl = np.log(np.array([0.25, 0.25, 0.5]))
+    band = lambda u: ar.resample_band(tl, None, u, 1e-5)
+    for u, tok in ((0.0, 0), (0.1, 0), (0.2499, 0), (0.2501, 1), (0.3, 1), (0.4999, 1), (0.5001, 2), (0.99, 2)):
+        assert band(u) == (tok, tok), u
+        assert ar.inverse_cdf(ar.softmax(tl), u) == tok
+    for u in (0.25, 0.25 - 0.9e-5, 0.25 + 0.9e-5):
+        assert band(u) == (0, 1), u
+    for u in (0.5, 0.5 - 0.9e-5, 0.5 + 0.9e-5):
+        assert band(u) == (1, 2), u
+    assert band(0.25 - 1.1e-5) == (0, 0) and band(0.25 + 1.1e-5) == (1, 1)
+    assert band(0.5 - 1.1e-5) == (1, 1) and band(0.5 + 1.1e-5) == (2, 2)
+    # the band scales with the total mass: residual max(0, p - q) with q = [1/4, 0, 1/4] is [0, 1/4, 1/4], total 1/2
+    q = np.array([0.25, 0.0, 0.25])
+    band_r = lambda u: ar.resample_band(tl, q, u, 1e-5)
+    assert band_r(0.3) == (1, 1) and band_r(0.7) == (2, 2)
+    assert band_r(0.5 + 0.9e-5) == (1, 2) and band_r(0.5 + 1.1e-5) == (2, 2) and band_r(0.5 - 1.1e-5) == (1, 1)
+    # a token without weight between two edges widens the index range but is never a valid answer:
+    # the comparison helper rejects it through its w > 0 test
+    tl0 = np.log(np.array([0.5, 1e-300, 0.5]))
+    tl0[1] = -np.inf
+    assert ar.resample_band(tl0, None, 0.5, 1e-5) == (0, 2) and ar.softmax(tl0)[1] == 0.0

@@ -40,16 +40,26 @@ def test_groups_are_independent():
     assert changed[0, :128].all()
 
 
-def test_result_is_rounded_to_bf16_like_the_generators_round():
+def test_result_is_rounded_to_bf16_as_torch_rounds():
+    """The dequantised weight is (code - zero) * scale rounded once to bfloat16, ties to even: checked against
+    torch's own float32 -> bfloat16 conversion (a library routine, not this repository's rounding expression)
+    and on hand-made values that sit exactly on a tie."""
+    import torch
     rng = np.random.default_rng(2)
     codes = rng.integers(0, 16, (8, 256)).astype(np.uint8)
     zeros = rng.integers(0, 16, (8, 2)).astype(np.uint8)
-    scales = synth.round_to_bf16(rng.uniform(0.001, 0.02, (8, 2)).astype(np.float32))
+    scales = torch.from_numpy(rng.uniform(0.001, 0.02, (8, 2)).astype(np.float32)).to(torch.bfloat16).float().numpy()
     out = quant.dequant_w4(codes, scales, zeros)
     # (code - zero) * scale has at most 5 + 8 significant bits: exact in float32, then rounded once
     exact32 = (codes.astype(np.float32) - np.repeat(zeros, 128, axis=1).astype(np.float32)) * np.repeat(scales, 128, axis=1)
-    assert np.array_equal(out, synth.round_to_bf16(exact32).astype(np.float64))
-    assert np.array_equal(synth.round_to_bf16(out.astype(np.float32)).astype(np.float64), out)   # bf16 values
+    want = torch.from_numpy(exact32).to(torch.bfloat16).float().numpy().astype(np.float64)
+    assert np.array_equal(out, want)
+    # by hand: scale 1 + 2^-7 (a bf16 value).  Code 3: 3.0234375 lies exactly halfway between the bf16 neighbours
+    # 3.015625 and 3.03125 (step 2^-6); the tie goes to the even mantissa, 3.03125.  Code 5: 5.0390625 is a
+    # quarter step (step 2^-5) above 5.03125 and rounds down to it.
+    c = np.zeros((1, 128), np.uint8); c[0, 0], c[0, 1] = 3, 5
+    got = quant.dequant_w4(c, np.array([[1.0 + 2.0 ** -7]], np.float32), np.zeros((1, 1), np.uint8))
+    assert got[0, 0] == 3.03125 and got[0, 1] == 5.03125 and got[0, 2] == 0.0
 
 
 def test_synthetic_checkpoint_is_within_half_a_step():
