@@ -87,7 +87,9 @@ size_t gs_accept_workspace_bytes(int n_servers, int n_rows, int vocab);
  * The draw returns the smallest token whose running sum of weights exceeds
  * u * (total weight), tokens in index order; a zero-weight token is never
  * returned.  If max(0, p - q) has no mass the draw falls back to p.
- * Errors: GS_EINVAL (null pointers, N <= 0, vocab <= 0, gamma < 0),
+ * Token ids are device data, so they cannot be checked before the launch: a server with a draft token id
+ * outside [0, V) gets accepted_len = -1 (the id is never used as an index; its next_token is drawn as for m = 0).
+ * Errors: GS_EINVAL (null pointers, N <= 0, vocab <= 0, gamma < 0, more than 2^22 rows),
  * GS_ECAPACITY (workspace too small), GS_EDEVICE.
  */
 gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
@@ -111,7 +113,8 @@ gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_r
  *   gamma_next   host [N]  out: maximiser of sum_i (1/X_i) (1 - a_i^(S_i+1))/(1 - a_i)
  *                          subject to sum S_i <= capacity, gamma_min <= S_i <= gamma_max
  * alpha_hat is clamped to [1e-6, 1-1e-6] inside the solve only.  gamma_max < 0
- * means unbounded.  Ties go to the lowest server index.
+ * means unbounded.  The gain of a server's next slot is formed as (1/X) * pow(a, S + 1) in double; equal
+ * gains go to the lowest server index.
  * Errors: GS_EINVAL (null, n <= 0, eta/beta outside [0,1], X <= 0 after update,
  * capacity < n * gamma_min, gamma_min < 0).
  */
@@ -119,6 +122,16 @@ gs_status gs_schedule_gamma(int n, const int* accepted_len, const float* accept_
                             const int* gamma_prev, double* alpha_hat, double* x_smooth,
                             double eta, double beta, int capacity, int gamma_min, int gamma_max,
                             int* gamma_next);
+
+/*
+ * The two baseline allocation policies the paper compares GoodSpeed with (Section IV-A, Baselines).  Host code.
+ *   gs_allocate_fixed   Fixed-S: capacity / n drafts for every server, the remainder to the lowest indices
+ *   gs_allocate_random  Random-S: each of the `capacity` draft slots goes to server floor(u * n), u = uniforms[k]
+ *                       (host [capacity], each in [0, 1))
+ * gamma_next host [n], out.  Errors: GS_EINVAL.
+ */
+gs_status gs_allocate_fixed(int n, int capacity, int* gamma_next);
+gs_status gs_allocate_random(int n, int capacity, const float* uniforms, int* gamma_next);
 
 /* ------------------------------------------------------------------------- */
 /* Batched verification step: decoder forward + rejection-verification          */
@@ -233,6 +246,19 @@ size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int 
 gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* batch,
                           const gs_accept_out* out, float* logits_out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Debug aid.  gs_verify_batch trusts the device-resident parts of a batch (it cannot read them without
+ * waiting for the GPU): cu_rows and ctx_len must equal their host copies, token ids must lie in [0, vocab) and
+ * the block-table entries that cover ctx_len + T_i tokens must name pages of the cache.  gs_check_batch
+ * verifies exactly that with one small kernel, SYNCHRONISES the stream, and returns GS_EINVAL with a
+ * message naming the first violation (GS_OK if there is none).  Call it while bringing up a caller, not in
+ * the serving loop.  workspace: dev, at least 4 * (2 N + 4) bytes.  Without the check, an out-of-range
+ * token id is clamped into the vocabulary by the embedding gather and reported as accepted_len = -1 by the
+ * accept stage when it is a draft token; a wrong page id or row offset is read as given.
+ */
+gs_status gs_check_batch(const gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* batch, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
 
 /* Test aid: with a non-NULL `trace` (dev, fp32 [(n_layers + 1)][R][d_model], caller-owned),
  * every later gs_verify_batch on this ctx also copies the residual stream entering each decoder

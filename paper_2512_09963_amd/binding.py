@@ -22,8 +22,9 @@ _DTYPES = {"f32": GS_F32, "bf16": GS_BF16, "w4": GS_W4}
 GS_ESHAPE = -2
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
-EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_schedule_gamma",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
+EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject",
+           "gs_schedule_gamma", "gs_allocate_fixed", "gs_allocate_random",
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -80,6 +81,10 @@ def lib():
         L.gs_schedule_gamma.restype = C.c_int
         L.gs_schedule_gamma.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_double, C.c_double, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        L.gs_allocate_fixed.restype = C.c_int
+        L.gs_allocate_fixed.argtypes = [C.c_int, C.c_int, C.c_void_p]
+        L.gs_allocate_random.restype = C.c_int
+        L.gs_allocate_random.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         if hasattr(L, "gs_create"):
             L.gs_create.restype = C.c_int
             L.gs_create.argtypes = [C.POINTER(gs_model_desc), C.POINTER(gs_weights), C.POINTER(C.c_void_p)]
@@ -90,6 +95,9 @@ def lib():
             L.gs_verify_batch.restype = C.c_int
             L.gs_verify_batch.argtypes = [C.c_void_p, C.POINTER(gs_kv_cache), C.POINTER(gs_batch),
                                           C.POINTER(gs_accept_out), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+            L.gs_check_batch.restype = C.c_int
+            L.gs_check_batch.argtypes = [C.c_void_p, C.POINTER(gs_kv_cache), C.POINTER(gs_batch), C.c_void_p,
+                                         C.c_size_t, C.c_void_p]
             L.gs_profile_enable.restype = C.c_int
             L.gs_profile_enable.argtypes = [C.c_void_p, C.c_int]
             L.gs_pack_weight.restype = C.c_int
@@ -170,6 +178,23 @@ def gs_schedule_gamma(accepted_len, accept_stat, gamma_prev, alpha_hat, x_smooth
     return nxt
 
 
+def gs_allocate_fixed(n, capacity):
+    """Fixed-S: the even split of the capacity (int32 array [n])."""
+    nxt = np.zeros(int(n), dtype=np.int32)
+    _check(lib().gs_allocate_fixed(int(n), int(capacity), nxt.ctypes.data))
+    return nxt
+
+
+def gs_allocate_random(n, capacity, uniforms):
+    """Random-S: slot k goes to server floor(uniforms[k] * n) (int32 array [n])."""
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    if u.size < int(capacity):
+        raise ValueError("one uniform per draft slot is needed")
+    nxt = np.zeros(int(n), dtype=np.int32)
+    _check(lib().gs_allocate_random(int(n), int(capacity), u.ctypes.data, nxt.ctypes.data))
+    return nxt
+
+
 def gs_pack_weight_w4(codes, scales, zeros, stream=None):
     """codes uint8 [N, K], scales bf16 [N, K/128], zeros uint8 [N, K/128] (device tensors) -> packed uint8
     device tensor in the layout the 4-bit projection kernel streams."""
@@ -237,6 +262,17 @@ class Verifier:
 
     def gs_workspace_bytes(self, max_rows, max_servers, max_ctx):
         return int(lib().gs_workspace_bytes(self._ctx, max_rows, max_servers, max_ctx))
+
+    def gs_check_batch(self, k_pages, v_pages, page_size, n_pages, gamma_host, ctx_len_host, cu_rows, ctx_len, tokens,
+                       block_table, workspace, stream=None):
+        """Debug check of the device-resident descriptor; raises GsError(GS_EINVAL) naming the first violation."""
+        g = _host_i32(gamma_host)
+        cl = _host_i32(ctx_len_host)
+        kv = gs_kv_cache(_ptr(k_pages), _ptr(v_pages), int(page_size), int(n_pages))
+        b = gs_batch(int(g.size), g.ctypes.data, cl.ctypes.data, _ptr(cu_rows).value, _ptr(ctx_len).value,
+                     _ptr(tokens).value, _ptr(block_table).value, int(block_table.shape[1]), None, None, None)
+        _check(lib().gs_check_batch(self._ctx, C.byref(kv), C.byref(b), _ptr(workspace), workspace.numel(),
+                                    _stream(stream)))
 
     def gs_verify_batch(self, k_pages, v_pages, page_size, n_pages, gamma_host, ctx_len_host, cu_rows, ctx_len,
                         tokens, block_table, q_probs, u_accept, u_resample, out, logits_out, workspace, stream=None):

@@ -8,8 +8,8 @@ the loop needs to compare allocation policies:
 
   goodspeed  gs_schedule_gamma: smoothed acceptance rates and goodputs, then the gradient allocation
              (Section III-C)
-  fixed      the capacity split evenly and never changed (Fixed-S of Section IV-A)
-  random     the capacity dealt to servers uniformly at random every round (Random-S of Section IV-A)
+  fixed      gs_allocate_fixed: the capacity split evenly and never changed (Fixed-S of Section IV-A)
+  random     gs_allocate_random: the capacity dealt to servers uniformly at random every round (Random-S)
 
 Runs on the HIP library only; there is no CPU path here.
 """
@@ -50,15 +50,13 @@ class LoopResult:
 
 
 def even_split(capacity, n):
-    base, extra = divmod(int(capacity), n)
-    return np.array([base + (1 if i < extra else 0) for i in range(n)], dtype=np.int32)
+    """Fixed-S (library call)."""
+    return gsb.gs_allocate_fixed(n, capacity)
 
 
 def random_split(capacity, n, uniforms):
-    g = np.zeros(n, dtype=np.int32)
-    for u in uniforms[:capacity]:
-        g[min(n - 1, int(float(u) * n))] += 1
-    return g
+    """Random-S (library call)."""
+    return gsb.gs_allocate_random(n, capacity, uniforms)
 
 
 def run(policy, sigmas, capacity, vocab, n_rounds, seed=synth.MASTER_SEED, eta=0.2, beta=0.5, alpha0=0.5, x0=1.0,

@@ -24,6 +24,11 @@ constexpr int kStatsThreads = 256;
 constexpr int kTileThreads = 256;
 constexpr int kTileElems = 2048;              // 256 lanes x 8 tokens
 constexpr int kMaxChunks = 64;
+}  // namespace
+// Rows and servers are laid out along gridDim.x (chunks or tile groups fastest), which HIP bounds by
+// 2^31 - 1 workgroups: 2^22 rows of at most 64 chunks stay below it.
+constexpr long kMaxAcceptRows = 1L << 22;
+namespace {
 
 struct Decision {    // per server, written by decide, read by the draw kernels
   int row;           // target row the extra token is drawn from (first row + m)
@@ -50,12 +55,13 @@ __device__ __forceinline__ float4 stream_load4(const float4* p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// row_stats: grid (chunks, rows).  VEC: rows are 16-byte aligned and V % 4 == 0.
+// row_stats: grid chunks * rows (chunk fastest).  VEC: rows are 16-byte aligned and V % 4 == 0.
 // ---------------------------------------------------------------------------------------
 template <bool VEC>
 __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* __restrict__ logits, int vocab,
-                                                                   int chunk_len, float2* __restrict__ partial) {
-  const int chunk = blockIdx.x, row = blockIdx.y, n_chunks = gridDim.x;
+                                                                   int chunk_len, int n_chunks,
+                                                                   float2* __restrict__ partial) {
+  const int row = blockIdx.x / n_chunks, chunk = blockIdx.x - row * n_chunks;
   const int begin = chunk * chunk_len;
   const int end = min(vocab, begin + chunk_len);
   const float* base = logits + (size_t)row * vocab;
@@ -202,9 +208,14 @@ __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict
   const int d0 = row0 - srv;
   int first_reject = gamma;    // smallest rejected draft index seen by this lane
   float stat = 0.f;
+  bool bad_id = false;         // a draft token id outside the vocabulary: never used as an index
   for (int j = lane; j < gamma; j += 64) {
     const int row = row0 + j;
-    const int tok = draft_tokens[d0 + j];
+    int tok = draft_tokens[d0 + j];
+    if (tok < 0 || tok >= vocab) {
+      bad_id = true;
+      tok = 0;
+    }
     const float u = u_accept[d0 + j];
     const float lg = logits[(size_t)row * vocab + tok];
     const float q = q_probs[(size_t)(d0 + j) * vocab + tok];
@@ -220,9 +231,10 @@ __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict
     first_reject = min(first_reject, __shfl_xor(first_reject, off));
     stat += __shfl_xor(stat, off);
   }
-  const int m_acc = first_reject;
+  const bool any_bad = __any(bad_id);      // (all 64 lanes of the wave are here)
+  const int m_acc = any_bad ? 0 : first_reject;
   if (write_out && lane == 0) {
-    accepted_len[srv] = m_acc;
+    accepted_len[srv] = any_bad ? -1 : m_acc;
     accept_stat[srv] = gamma > 0 ? stat / (float)gamma : 0.f;
   }
   Decision d;
@@ -236,14 +248,14 @@ __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict
 }
 
 // ---------------------------------------------------------------------------------------
-// draw_tiles: grid (tile groups, servers), 256 lanes.  A workgroup owns kTilesPerGroup
+// draw_tiles: grid tile groups * servers (group fastest), 256 lanes.  A workgroup owns kTilesPerGroup
 // consecutive 2048-token tiles; group 0 also stores the server's outputs and its decision.
 // ---------------------------------------------------------------------------------------
 constexpr int kTilesPerGroup = 4;
 
 template <bool VEC>
 __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __restrict__ cu_rows, int vocab,
-                                                                  int n_chunks, int n_tiles,
+                                                                  int n_chunks, int n_tiles, int n_groups,
                                                                   const float2* __restrict__ partial,
                                                                   const float* __restrict__ logits,
                                                                   const float* __restrict__ q_probs,
@@ -254,7 +266,7 @@ __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __r
                                                                   float* __restrict__ ratio_out,
                                                                   Decision* __restrict__ decision,
                                                                   double* __restrict__ tile_sums) {
-  const int group = blockIdx.x, srv = blockIdx.y;
+  const int srv = blockIdx.x / n_groups, group = blockIdx.x - srv * n_groups;
   __shared__ Decision sh_d;
   __shared__ double part[kTileThreads / 64];
   if (threadIdx.x < 64) {
@@ -480,15 +492,16 @@ gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab
   AcceptPlan p = plan_accept(n_servers, n_rows, vocab, workspace);
   const bool vec = (vocab % 4 == 0) && (reinterpret_cast<uintptr_t>(target_logits) % 16 == 0) &&
                    (q_probs == nullptr || reinterpret_cast<uintptr_t>(q_probs) % 16 == 0);
-  dim3 g1(p.n_chunks, n_rows);
+  const unsigned g1 = (unsigned)p.n_chunks * (unsigned)n_rows;
   if (vec)
-    row_stats_kernel<true><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.partial);
+    row_stats_kernel<true><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.n_chunks, p.partial);
   else
-    row_stats_kernel<false><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.partial);
+    row_stats_kernel<false><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.n_chunks, p.partial);
   GS_LAUNCH_CHECK("row_stats");
-  dim3 g2(ceil_div(p.n_tiles, kTilesPerGroup), n_servers);
+  const int n_groups = ceil_div(p.n_tiles, kTilesPerGroup);
+  const unsigned g2 = (unsigned)n_groups * (unsigned)n_servers;
   if (vec) {
-    draw_tiles_kernel<true><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, p.partial,
+    draw_tiles_kernel<true><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, n_groups, p.partial,
                                                              target_logits, q_probs, draft_tokens, u_accept,
                                                              out->accepted_len, out->accept_stat, out->ratio,
                                                              p.decision, p.tile_sums);
@@ -496,7 +509,7 @@ gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab
     pick_token_kernel<true><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
                                                                     q_probs, p.tile_sums, u_resample, out->next_token);
   } else {
-    draw_tiles_kernel<false><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, p.partial,
+    draw_tiles_kernel<false><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, n_groups, p.partial,
                                                               target_logits, q_probs, draft_tokens, u_accept,
                                                               out->accepted_len, out->accept_stat, out->ratio,
                                                               p.decision, p.tile_sums);
@@ -534,7 +547,7 @@ extern "C" gs_status gs_accept_reject(int n_servers, const int* gamma_host, cons
     n_rows += gamma_host[i] + 1;
     n_draft += gamma_host[i];
   }
-  if (n_rows > 0x3fffffff) return gs::fail(GS_EINVAL, "too many rows");
+  if (n_rows > gs::kMaxAcceptRows) return gs::fail(GS_EINVAL, "too many rows (at most %ld)", gs::kMaxAcceptRows);
   if (n_draft > 0 && (!q_probs || !draft_tokens || !u_accept))
     return gs::fail(GS_EINVAL, "q_probs, draft_tokens and u_accept are required when any gamma > 0");
   if (workspace_bytes < gs::accept_workspace_bytes(n_servers, (int)n_rows, vocab))

@@ -32,9 +32,10 @@ __device__ __forceinline__ int server_of_row(const int* __restrict__ cu_rows, in
 
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ embed, const int* __restrict__ tokens,
-                                                    float* __restrict__ x, int d) {
+                                                    float* __restrict__ x, int d, int vocab) {
   const int r = blockIdx.x;
-  const T* src = embed + (size_t)tokens[r] * d;
+  const int tok = min(max(tokens[r], 0), vocab - 1);      // an id outside the vocabulary is never used as an index
+  const T* src = embed + (size_t)tok * d;
   for (int i = threadIdx.x; i < d; i += 256) x[(size_t)r * d + i] = Storage<T>::load(src + i);
 }
 
@@ -202,9 +203,9 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ g
     __VA_ARGS__                                   \
   }
 
-gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d,
+gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, int vocab,
                        hipStream_t stream) {
-  GS_DISPATCH_T(dtype, embed_kernel<T><<<n_rows, 256, 0, stream>>>(static_cast<const T*>(embed), tokens, x, d);)
+  GS_DISPATCH_T(dtype, embed_kernel<T><<<n_rows, 256, 0, stream>>>(static_cast<const T*>(embed), tokens, x, d, vocab);)
   GS_LAUNCH_CHECK("embed");
   return GS_OK;
 }

@@ -73,9 +73,7 @@ extern "C" gs_status gs_schedule_gamma(int n, const int* accepted_len, const flo
     gamma_next[i] = gamma_min;
     left -= gamma_min;
     if (gamma_max < 0 || gamma_min < gamma_max) {
-      double g = 1.0 / x_smooth[i];
-      for (int k = 0; k <= gamma_min; ++k) g *= a[i];   // (1/X) a^(gamma_min + 1)
-      heap.push({g, i});
+      heap.push({(1.0 / x_smooth[i]) * std::pow(a[i], (double)(gamma_min + 1)), i});
     }
   }
   while (left > 0 && !heap.empty()) {
@@ -83,7 +81,30 @@ extern "C" gs_status gs_schedule_gamma(int n, const int* accepted_len, const flo
     heap.pop();
     gamma_next[s.server] += 1;
     --left;
-    if (gamma_max < 0 || gamma_next[s.server] < gamma_max) heap.push({s.gain * a[s.server], s.server});
+    // next gain formed from scratch as (1/X) a^(S + 1): the same expression for every S, so that two servers
+    // with equal (alpha_hat, X) always tie exactly (a running product would depend on the path)
+    if (gamma_max < 0 || gamma_next[s.server] < gamma_max)
+      heap.push({(1.0 / x_smooth[s.server]) * std::pow(a[s.server], (double)(gamma_next[s.server] + 1)), s.server});
+  }
+  return GS_OK;
+}
+
+// Baseline allocation policies of the paper's comparison (Section IV-A): Fixed-S and Random-S.
+extern "C" gs_status gs_allocate_fixed(int n, int capacity, int* gamma_next) {
+  if (n <= 0 || capacity < 0 || !gamma_next) return gs::fail(GS_EINVAL, "n must be positive, capacity non-negative");
+  for (int i = 0; i < n; ++i) gamma_next[i] = capacity / n + (i < capacity % n ? 1 : 0);
+  return GS_OK;
+}
+
+extern "C" gs_status gs_allocate_random(int n, int capacity, const float* uniforms, int* gamma_next) {
+  if (n <= 0 || capacity < 0 || !gamma_next || (capacity > 0 && !uniforms))
+    return gs::fail(GS_EINVAL, "n must be positive, capacity non-negative, uniforms given");
+  for (int k = 0; k < capacity; ++k)
+    if (!(uniforms[k] >= 0.f && uniforms[k] < 1.f)) return gs::fail(GS_EINVAL, "uniforms[%d] is outside [0, 1)", k);
+  for (int i = 0; i < n; ++i) gamma_next[i] = 0;
+  for (int k = 0; k < capacity; ++k) {
+    int i = (int)((double)uniforms[k] * (double)n);
+    gamma_next[i < n ? i : n - 1] += 1;
   }
   return GS_OK;
 }

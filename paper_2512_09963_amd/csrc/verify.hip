@@ -18,7 +18,8 @@ gs_status launch_pack_weight_w4(const void* q, const void* scales, const void* z
 gs_status launch_gemm(int dtype, const void* X, const void* W, float* P, int M, int N, int K, hipStream_t stream);
 bool gate_up_fused(int dtype, int M, int F, int K);
 gs_status launch_gemm_gate_up(const void* X, const void* W, void* act, int M, int F, int K, hipStream_t stream);
-gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, hipStream_t);
+gs_status launch_embed(int dtype, const void* embed, const int* tokens, float* x, int n_rows, int d, int vocab,
+                       hipStream_t);
 gs_status launch_add_rmsnorm(int dtype, float* x, const float* partial, int n_splits, int n_rows, const float* w,
                              float eps, void* h, int d, hipStream_t stream);
 gs_status launch_row_meta(const int* cu_rows, const int* ctx_len, int n_servers, int n_rows, const int* block_table,
@@ -151,6 +152,43 @@ __global__ void gather_draft_tokens_kernel(const int* __restrict__ tokens, const
   const int srv = blockIdx.x;
   const int r0 = cu_rows[srv], gamma = cu_rows[srv + 1] - r0 - 1;
   for (int j = threadIdx.x; j < gamma; j += blockDim.x) draft_tokens[r0 - srv + j] = tokens[r0 + 1 + j];
+}
+
+// Debug check of the device-resident descriptor (gs_check_batch).  One workgroup per server; the first
+// inconsistency found is recorded as (kind, server, index, value) with a compare-and-swap on err[0].
+enum { kBadCuRows = 1, kBadCtxLen = 2, kBadToken = 3, kBadPage = 4 };
+__global__ __launch_bounds__(256) void check_batch_kernel(const int* __restrict__ cu_rows,
+                                                          const int* __restrict__ ctx_len,
+                                                          const int* __restrict__ tokens,
+                                                          const int* __restrict__ block_table, int max_blocks,
+                                                          const int* __restrict__ gamma_ref,     // device copies of the
+                                                          const int* __restrict__ ctx_ref,       // host arrays
+                                                          int vocab, int n_pages, int page_size, int* __restrict__ err) {
+  const int srv = blockIdx.x;
+  int row0 = 0;
+  for (int i = 0; i < srv; ++i) row0 += gamma_ref[i] + 1;
+  const int T = gamma_ref[srv] + 1;
+  auto report = [&](int kind, int index, int value) {
+    if (atomicCAS(&err[0], 0, kind) == 0) {
+      err[1] = srv;
+      err[2] = index;
+      err[3] = value;
+    }
+  };
+  if (threadIdx.x == 0) {
+    if (cu_rows[srv] != row0) report(kBadCuRows, srv, cu_rows[srv]);
+    else if (cu_rows[srv + 1] != row0 + T) report(kBadCuRows, srv + 1, cu_rows[srv + 1]);
+    if (ctx_len[srv] != ctx_ref[srv]) report(kBadCtxLen, srv, ctx_len[srv]);
+  }
+  for (int j = threadIdx.x; j < T; j += blockDim.x) {
+    const int t = tokens[row0 + j];
+    if (t < 0 || t >= vocab) report(kBadToken, row0 + j, t);
+  }
+  const int n_blocks = (ctx_ref[srv] + T + page_size - 1) / page_size;     // <= max_blocks (checked on the host)
+  for (int blk = threadIdx.x; blk < n_blocks; blk += blockDim.x) {
+    const int pg = block_table[(size_t)srv * max_blocks + blk];
+    if (pg < 0 || pg >= n_pages) report(kBadPage, blk, pg);
+  }
 }
 
 }  // namespace
@@ -370,7 +408,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     GS_TRY(call);               \
     GS_TRY(timer.end());        \
   } while (0)
-  GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(act, ctx->embed, b->tokens, p.x, rows, d, stream));
+  GS_STAGE(GS_STAGE_GLUE, gs::launch_embed(act, ctx->embed, b->tokens, p.x, rows, d, m.vocab, stream));
   GS_STAGE(GS_STAGE_GLUE, gs::launch_row_meta(b->cu_rows, b->ctx_len, n, rows, b->block_table, b->max_blocks, kv->page_size,
                                               m.head_dim, m.rope_theta, p.row_slot, p.rope, stream));
   if (act == GS_BF16)
@@ -429,4 +467,41 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
 #undef GS_STAGE
 #undef GS_TRY
   return GS_OK;
+}
+
+extern "C" gs_status gs_check_batch(const gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* b, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  if (!ctx || !kv || !b || !workspace) return gs::fail(GS_EINVAL, "null argument");
+  const int n = b->n_servers;
+  if (n <= 0) return gs::fail(GS_EINVAL, "n_servers must be positive");
+  if (!b->gamma_host || !b->ctx_len_host || !b->cu_rows || !b->ctx_len || !b->tokens || !b->block_table)
+    return gs::fail(GS_EINVAL, "null batch field");
+  if (kv->page_size <= 0 || kv->n_pages <= 0 || b->max_blocks <= 0) return gs::fail(GS_EINVAL, "invalid KV cache descriptor");
+  for (int i = 0; i < n; ++i) {
+    const int g = b->gamma_host[i], L = b->ctx_len_host[i];
+    if (g < 0 || L < 0) return gs::fail(GS_EINVAL, "server %d: gamma = %d, ctx_len = %d", i, g, L);
+    if (((long)L + g + 1 + kv->page_size - 1) / kv->page_size > b->max_blocks)
+      return gs::fail(GS_ECAPACITY, "server %d needs more KV blocks than the block table has", i);
+  }
+  const size_t need = sizeof(int) * (2 * (size_t)n + 4);
+  if (workspace_bytes < need) return gs::fail(GS_ECAPACITY, "workspace of %zu bytes, the check needs %zu", workspace_bytes, need);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int* dev = static_cast<int*>(workspace);          // [4] error record, [n] gamma, [n] ctx_len
+  const int zero[4] = {0, 0, 0, 0};
+  GS_HIP_CHECK(hipMemcpyAsync(dev, zero, sizeof(zero), hipMemcpyHostToDevice, stream));
+  GS_HIP_CHECK(hipMemcpyAsync(dev + 4, b->gamma_host, sizeof(int) * n, hipMemcpyHostToDevice, stream));
+  GS_HIP_CHECK(hipMemcpyAsync(dev + 4 + n, b->ctx_len_host, sizeof(int) * n, hipMemcpyHostToDevice, stream));
+  check_batch_kernel<<<n, 256, 0, stream>>>(b->cu_rows, b->ctx_len, b->tokens, b->block_table, b->max_blocks, dev + 4,
+                                            dev + 4 + n, ctx->desc.vocab, kv->n_pages, kv->page_size, dev);
+  GS_LAUNCH_CHECK("check_batch");
+  int err[4] = {0, 0, 0, 0};
+  GS_HIP_CHECK(hipMemcpyAsync(err, dev, sizeof(err), hipMemcpyDeviceToHost, stream));
+  GS_HIP_CHECK(hipStreamSynchronize(stream));
+  switch (err[0]) {
+    case 0: return GS_OK;
+    case kBadCuRows: return gs::fail(GS_EINVAL, "device cu_rows[%d] = %d does not match gamma_host", err[2], err[3]);
+    case kBadCtxLen: return gs::fail(GS_EINVAL, "device ctx_len[%d] = %d does not match ctx_len_host", err[2], err[3]);
+    case kBadToken: return gs::fail(GS_EINVAL, "tokens[%d] = %d of server %d is outside the vocabulary", err[2], err[3], err[1]);
+    default: return gs::fail(GS_EINVAL, "block_table[%d][%d] = %d is not a page of the cache", err[1], err[2], err[3]);
+  }
 }

@@ -88,6 +88,16 @@ def test_accept_reject_validates_on_the_host_before_any_launch():
     assert rc == -3
 
 
+def test_accept_reject_rejects_more_rows_than_a_grid_holds():
+    import ctypes as C
+    L = gsb.lib()
+    n = 3000
+    g = np.full(n, 2000, dtype=np.int32)             # 6 million rows
+    out = gsb.gs_accept_out(8, 8, 8, None)
+    rc = L.gs_accept_reject(n, g.ctypes.data, 8, 1024, 8, 8, 8, 8, 8, C.byref(out), 8, 1 << 40, None)
+    assert rc == -1 and b"too many rows" in L.gs_last_error()
+
+
 def test_baseline_allocation_policies_of_the_loop_equal_the_oracle():
     """Host logic of the closed loop: the even and the random split (no GPU involved)."""
     from oracle import closed_loop as ol

@@ -247,3 +247,54 @@ def test_verify_batch_rejects_bad_descriptors():
         gsb.Verifier(dict(n_layers=1, d_model=100, n_heads=3, n_kv_heads=2, head_dim=64, d_ffn=256, vocab=512,
                           rope_theta=1e4, rms_eps=1e-5, dtype="f32"), ver._keep[0], ver._keep[1])
     assert e.value.code == -2
+
+
+def test_check_batch_names_the_first_violation_and_bad_token_ids_are_never_used_as_indices():
+    """gs_check_batch (debug aid) against deliberately inconsistent device-side descriptors, each of which
+    the kernels' own guards keep in bounds; and the documented behaviour of gs_verify_batch without the check:
+    a draft token id outside the vocabulary gives accepted_len = -1 for that server only."""
+    import torch
+    from paper_2512_09963_amd import binding as gsb, workload as wl
+    ms = synth.ModelShape(1, 128, 2, 2, 64, 256, 512, 10000.0, dtype="bf16")
+    top, layers = _model(ms, 5, 0.08)
+    ver = wl.upload_model(ms, top, lambda l: layers[l])
+    batch = synth.make_batch(5, np.array([2, 3, 1], np.int32), np.array([10, 40, 3], np.int32), 16)
+    tokens, q, ua, ur = synth.verify_side_inputs(5, ms.vocab, batch.gamma)
+    kv = wl.KVCache(ms, batch.n_pages, 16)
+    db = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
+
+    def check(d):
+        ver.gs_check_batch(kv.k, kv.v, kv.page_size, kv.n_pages, d.gamma, d.ctx_len_host, d.cu_rows, d.ctx_len,
+                           d.tokens, d.block_table, ws)
+
+    check(db)                                            # consistent: passes
+    good_out, good_logits, _ = wl.verify(ver, kv, db)
+    torch.cuda.synchronize()
+    good_m = good_out["accepted_len"].cpu().numpy().copy()
+
+    bad = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    bad.tokens[4] = ms.vocab + 5                         # server 1's first draft token
+    with pytest.raises(gsb.GsError) as e:
+        check(bad)
+    assert e.value.code == -1 and "tokens[4]" in str(e.value) and "vocabulary" in str(e.value)
+    out, _, _ = wl.verify(ver, kv, bad)                  # without the check: flagged, nothing read out of range
+    torch.cuda.synchronize()
+    m = out["accepted_len"].cpu().numpy()
+    assert m[1] == -1 and m[0] == good_m[0]
+
+    bad = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    bad.cu_rows[2] += 1
+    with pytest.raises(gsb.GsError) as e:
+        check(bad)
+    assert "cu_rows[2]" in str(e.value)
+    bad = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    bad.ctx_len[0] = 11
+    with pytest.raises(gsb.GsError) as e:
+        check(bad)
+    assert "ctx_len[0]" in str(e.value)
+    bad = wl.DeviceBatch(batch, tokens, q, ua, ur)
+    bad.block_table[1, 0] = batch.n_pages
+    with pytest.raises(gsb.GsError) as e:
+        check(bad)
+    assert "block_table[1][0]" in str(e.value)
