@@ -98,6 +98,25 @@ gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_r
                            const gs_accept_out* out, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
+/*
+ * gs_accept_reject for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * gs_accept_reject without the workspace; the kernels' scratch (chunk statistics, per-server decisions,
+ * tile sums) lives in a device array of GS_ACCEPT_STATIC_SCRATCH_BYTES that is part of the library image
+ * (every GPU the library runs on holds its own copy until the process ends).  The call allocates nothing
+ * and frees nothing.  Its first call on a device looks up the array's address on that device
+ * (hipGetSymbolAddress); make that call outside a graph capture.  All calls on one GPU share the array, which
+ * keeps the last call's contents (every word a call reads it has written itself first): calls that overlap
+ * in time on one GPU, on any streams, race.
+ * Errors: as gs_accept_reject; GS_ECAPACITY when gs_accept_workspace_bytes(n_servers, rows, vocab) exceeds
+ * GS_ACCEPT_STATIC_SCRATCH_BYTES (nothing is launched).
+ */
+#define GS_ACCEPT_STATIC_SCRATCH_BYTES (4u << 20)
+gs_status gs_accept_reject_static(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                                  const float* target_logits, const float* q_probs,
+                                  const int* draft_tokens, const float* u_accept, const float* u_resample,
+                                  const gs_accept_out* out, void* hip_stream);
+
 /* ------------------------------------------------------------------------- */
 /* Estimators and GoodSpeed-sched (paper Section III-C: the alpha-hat and X      */
 /* smoothing equations and the scheduling problem; Algorithm 1 orders the       */

@@ -16,6 +16,7 @@
 // Bandwidth-bound: row_stats streams 4*V bytes per target row; the draw touches O(N*V) bytes.
 #include "common.h"
 #include <cmath>
+#include <mutex>
 
 namespace gs {
 namespace {
@@ -554,4 +555,59 @@ extern "C" gs_status gs_accept_reject(int n_servers, const int* gamma_host, cons
     return gs::fail(GS_ECAPACITY, "workspace of %zu bytes is smaller than gs_accept_workspace_bytes", workspace_bytes);
   return gs::launch_accept(n_servers, (int)n_rows, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept,
                            u_resample, out, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------------------
+// gs_accept_reject_static: the same kernels with their workspace in a device array that is part of the
+// library image, for callers that cannot allocate.  The array's name is a host-side stand-in, not a
+// device address: its address on the current device is looked up once per device and kept.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[GS_ACCEPT_STATIC_SCRATCH_BYTES];
+
+namespace gs {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};     // device address of `scratch` per device, filled on first use
+
+gs_status static_scratch(void** out) {
+  int dev = -1;
+  GS_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(GS_EUNSUPPORTED, "device index %d is beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    GS_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(GS_EDEVICE, "hipGetSymbolAddress returned a null address for the static scratch");
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return GS_OK;
+}
+
+}  // namespace
+}  // namespace gs
+
+extern "C" gs_status gs_accept_reject_static(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                                             const float* target_logits, const float* q_probs,
+                                             const int* draft_tokens, const float* u_accept,
+                                             const float* u_resample, const gs_accept_out* out, void* hip_stream) {
+  if (n_servers <= 0 || vocab <= 0) return gs::fail(GS_EINVAL, "n_servers and vocab must be positive");
+  if (!gamma_host) return gs::fail(GS_EINVAL, "null argument");
+  long n_rows = 0;
+  for (int i = 0; i < n_servers; ++i) {
+    if (gamma_host[i] < 0) return gs::fail(GS_EINVAL, "gamma[%d] = %d is negative", i, gamma_host[i]);
+    n_rows += gamma_host[i] + 1;
+  }
+  if (n_rows > gs::kMaxAcceptRows) return gs::fail(GS_EINVAL, "too many rows");
+  const size_t need = gs::accept_workspace_bytes(n_servers, (int)n_rows, vocab);
+  if (need > GS_ACCEPT_STATIC_SCRATCH_BYTES)
+    return gs::fail(GS_ECAPACITY, "this batch needs %zu bytes of scratch, the static array holds %zu", need,
+                    (size_t)GS_ACCEPT_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  const gs_status st = gs::static_scratch(&ws);
+  if (st != GS_OK) return st;
+  return gs_accept_reject(n_servers, gamma_host, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept,
+                          u_resample, out, ws, GS_ACCEPT_STATIC_SCRATCH_BYTES, hip_stream);
 }

@@ -88,6 +88,20 @@ def test_accept_reject_validates_on_the_host_before_any_launch():
     assert rc == -3
 
 
+def test_static_scratch_entry_point_rejects_oversized_batches_on_the_host():
+    """gs_accept_reject_static: sizes beyond its array fail with GS_ECAPACITY before any HIP call."""
+    import ctypes as C
+    L = gsb.lib()
+    n = 4200
+    g = np.ones(n, dtype=np.int32)
+    assert L.gs_accept_workspace_bytes(n, 2 * n, 262144) > (4 << 20)
+    out = gsb.gs_accept_out(8, 8, 8, None)
+    rc = L.gs_accept_reject_static(n, g.ctypes.data, 8, 262144, 8, 8, 8, 8, 8, C.byref(out), None)
+    assert rc == -3 and b"static array" in L.gs_last_error()
+    g[7] = -1
+    assert L.gs_accept_reject_static(n, g.ctypes.data, 8, 262144, 8, 8, 8, 8, 8, C.byref(out), None) == -1
+
+
 def test_accept_reject_rejects_more_rows_than_a_grid_holds():
     import ctypes as C
     L = gsb.lib()
