@@ -111,8 +111,9 @@ def run_steps(w, n_steps, sched):
     return last
 
 
-def accept_leg(seed):
-    """gs_accept_reject alone: 64 servers x gamma 8 over vocab 151936, sigma = 1."""
+def accept_leg(seed, bf16=False):
+    """gs_accept_reject alone: 64 servers x gamma 8 over vocab 151936, sigma = 1 (bf16: the same inputs rounded
+    to bfloat16 through gs_accept_reject_bf16, half the bytes)."""
     import torch
     from paper_2512_09963_amd import binding as gsb, synth
     dev = torch.device("cuda:0")
@@ -120,8 +121,9 @@ def accept_leg(seed):
     gamma = np.full(N, g, np.int32)
     inp = synth.accept_inputs(seed, gamma, V, 1.0)
     R, G = N * (g + 1), N * g
-    tl0 = torch.from_numpy(inp.target_logits).to(dev)
-    q0 = torch.from_numpy(inp.q_probs).to(dev)
+    wide = torch.bfloat16 if bf16 else torch.float32
+    tl0 = torch.from_numpy(inp.target_logits).to(dev).to(wide)
+    q0 = torch.from_numpy(inp.q_probs).to(dev).to(wide)
     tok0 = torch.from_numpy(inp.draft_tokens).to(dev)
     ua = torch.from_numpy(inp.u_accept).to(dev)
     ur = torch.from_numpy(inp.u_resample).to(dev)
@@ -134,9 +136,11 @@ def accept_leg(seed):
     out = gsb.make_accept_out(N, G, dev, want_ratio=False)
     ws = torch.empty(gsb.gs_accept_workspace_bytes(N, R, V), dtype=torch.uint8, device=dev)
 
+    entry = gsb.gs_accept_reject_bf16 if bf16 else gsb.gs_accept_reject
+
     def call(k):
         tl, q, tok = sets[k % len(sets)]
-        gsb.gs_accept_reject(gamma, cu, V, tl, q, tok, ua, ur, out, ws)
+        entry(gamma, cu, V, tl, q, tok, ua, ur, out, ws)
 
     for k in range(10):
         call(k)
@@ -150,9 +154,9 @@ def accept_leg(seed):
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / iters
     n_rej = int((out["accepted_len"] < g).sum().item())
-    alg = 4.0 * V * (R + n_rej)
+    alg = (2.0 if bf16 else 4.0) * V * (R + n_rej)
     gbs = alg / us / 1e3
-    return {"workload": "accept/reject+resample, 64 servers x gamma 8, vocab 151936, fp32, sigma 1.0",
+    return {"workload": f"accept/reject+resample, 64 servers x gamma 8, vocab 151936, {'bf16' if bf16 else 'fp32'} inputs, sigma 1.0",
             "us_per_call": round(us, 2), "algorithmic_bytes": alg, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "rejecting_servers": n_rej}
 
@@ -297,6 +301,7 @@ def main():
         torch.cuda.synchronize()
     if not args.skip_accept_leg and args.workload == "cfg3":
         res["accept_kernel"] = accept_leg(seed)
+        res["accept_kernel_bf16_inputs"] = accept_leg(seed, bf16=True)
     if not args.skip_cpu_baseline and args.workload == "cfg3":
         res["cpu_baseline"] = cpu_baseline(ms, w, seed)
     print(json.dumps(res), flush=True)

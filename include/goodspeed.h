@@ -99,6 +99,21 @@ gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_r
                            void* hip_stream);
 
 /*
+ * The same rule on bfloat16 inputs (half the bytes of the bandwidth-bound pass): target_logits dev [R, V] and
+ * q_probs dev [G, V] hold bfloat16 bit patterns; everything else as gs_accept_reject, arithmetic in fp32.
+ * The inputs are taken as the exact numbers they encode: p = softmax of the bfloat16 logits, q the bfloat16
+ * values (which need not sum to one), so decisions and tokens are again defined exactly by the paper's rule
+ * (Section II-A-2) and held to the same parity bar.  What rounding q to bfloat16 costs the method is on the
+ * caller's side of the boundary: a draft token sampled from the unrounded q is accepted with probability
+ * min(1, p/q~) instead of min(1, p/q), so the law of the emitted token is no longer exactly p: it differs
+ * from p by less than 2^-8 in total variation (q~/q lies within 1 +- 2^-9).
+ */
+gs_status gs_accept_reject_bf16(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                                const void* target_logits, const void* q_probs, const int* draft_tokens,
+                                const float* u_accept, const float* u_resample, const gs_accept_out* out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * gs_accept_reject for callers that cannot allocate device memory or hand over a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
  * gs_accept_reject without the workspace; the kernels' scratch (chunk statistics, per-server decisions,
@@ -257,6 +272,8 @@ size_t gs_workspace_bytes(const gs_ctx* ctx, int max_rows, int max_servers, int 
  * that are dead and overwritten next round), then runs gs_accept_reject on the
  * resulting logits.
  *   logits_out  dev [R, V] fp32, or NULL to keep the logits in the workspace only
+ * For bf16 models whose LM-head projection runs as one launch, that projection also leaves every row's softmax
+ * statistics (max, sum exp) per column block, so the accept stage does not read the logits again for them.
  *   out->*      as for gs_accept_reject; if batch->q_probs is NULL the step stops
  *               after the logits (prefill use) and `out` may be NULL.
  * Errors: GS_EINVAL, GS_ECAPACITY (workspace; a block table too short for

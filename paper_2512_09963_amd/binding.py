@@ -22,7 +22,7 @@ _DTYPES = {"f32": GS_F32, "bf16": GS_BF16, "w4": GS_W4}
 GS_ESHAPE = -2
 _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4: "GS_EDEVICE", -5: "GS_EUNSUPPORTED"}
 
-EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_accept_reject_static",
+EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_accept_reject_bf16", "gs_accept_reject_static",
            "gs_schedule_gamma", "gs_allocate_fixed", "gs_allocate_random",
            "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
 STAGES = ["gemm", "attention", "glue", "accept"]
@@ -78,6 +78,8 @@ def lib():
         L.gs_accept_reject.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.POINTER(gs_accept_out), C.c_void_p, C.c_size_t,
                                        C.c_void_p]
+        L.gs_accept_reject_bf16.restype = C.c_int
+        L.gs_accept_reject_bf16.argtypes = L.gs_accept_reject.argtypes
         L.gs_accept_reject_static.restype = C.c_int
         L.gs_accept_reject_static.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(gs_accept_out),
@@ -163,6 +165,19 @@ def gs_accept_reject(gamma_host, cu_rows, vocab, target_logits, q_probs, draft_t
                                   _ptr(q_probs), _ptr(draft_tokens), _ptr(u_accept), _ptr(u_resample),
                                   C.byref(st), _ptr(workspace), workspace.numel() if workspace is not None else 0,
                                   _stream(stream)))
+    return out
+
+
+def gs_accept_reject_bf16(gamma_host, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept, u_resample,
+                          out, workspace, stream=None):
+    """gs_accept_reject on bfloat16 target_logits and q_probs (device tensors of dtype bfloat16)."""
+    assert target_logits.dtype == torch.bfloat16 and (q_probs is None or q_probs.dtype == torch.bfloat16)
+    g = _host_i32(gamma_host)
+    st = _accept_out_struct(out)
+    _check(lib().gs_accept_reject_bf16(int(g.size), g.ctypes.data, _ptr(cu_rows), int(vocab), _ptr(target_logits),
+                                       _ptr(q_probs), _ptr(draft_tokens), _ptr(u_accept), _ptr(u_resample),
+                                       C.byref(st), _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                       _stream(stream)))
     return out
 
 

@@ -15,6 +15,7 @@
 //               token whose running sum first exceeds u * total
 // Bandwidth-bound: row_stats streams 4*V bytes per target row; the draw touches O(N*V) bytes.
 #include "common.h"
+#include "device_types.h"
 #include <cmath>
 #include <mutex>
 
@@ -48,50 +49,83 @@ __device__ __forceinline__ void merge_pair(float& m, float& s, float m2, float s
 
 __device__ __forceinline__ float max4(const float4& v) { return fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)); }
 
-// 16-byte load that does not displace cache lines (the logits are read once)
+// Sixteen bytes of a row: 4 floats or 8 bfloat16, widened to float.  STREAM: the load does not displace
+// cache lines (the logits are read once by the statistics pass).
 typedef float __attribute__((ext_vector_type(4))) float4_vec;
-__device__ __forceinline__ float4 stream_load4(const float4* p) {
-  const float4_vec v = __builtin_nontemporal_load(reinterpret_cast<const float4_vec*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
+typedef unsigned int __attribute__((ext_vector_type(4))) uint4_vec;
+template <typename T> struct Pack;
+template <> struct Pack<float> {
+  static constexpr int W = 4;
+  template <bool STREAM>
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const float4_vec x = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const float4_vec*>(p))
+                                : *reinterpret_cast<const float4_vec*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+};
+template <> struct Pack<bf16_t> {
+  static constexpr int W = 8;
+  template <bool STREAM>
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4_vec x = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const uint4_vec*>(p))
+                               : *reinterpret_cast<const uint4_vec*>(p);
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+    v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+    v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+  }
+};
+template <int W>
+__device__ __forceinline__ float max_of(const float (&v)[W]) {
+  float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+  if constexpr (W == 8) m = fmaxf(m, fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+  return m;
+}
+template <int W>
+__device__ __forceinline__ float sum_exp_of(const float (&v)[W], float mm) {
+  float a = __expf(v[0] - mm) + __expf(v[1] - mm) + __expf(v[2] - mm) + __expf(v[3] - mm);
+  if constexpr (W == 8) a += __expf(v[4] - mm) + __expf(v[5] - mm) + __expf(v[6] - mm) + __expf(v[7] - mm);
+  return a;
 }
 
 // ---------------------------------------------------------------------------------------
 // row_stats: grid chunks * rows (chunk fastest).  VEC: rows are 16-byte aligned and V % 4 == 0.
 // ---------------------------------------------------------------------------------------
-template <bool VEC>
-__global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* __restrict__ logits, int vocab,
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const T* __restrict__ logits, int vocab,
                                                                    int chunk_len, int n_chunks,
                                                                    float2* __restrict__ partial) {
+  constexpr int W = Pack<T>::W;
   const int row = blockIdx.x / n_chunks, chunk = blockIdx.x - row * n_chunks;
   const int begin = chunk * chunk_len;
   const int end = min(vocab, begin + chunk_len);
-  const float* base = logits + (size_t)row * vocab;
+  const T* base = logits + (size_t)row * vocab;
   float m = -INFINITY, s = 0.f;
-  const float4 neg = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
 
   if (VEC) {
-    const float4* p = reinterpret_cast<const float4*>(base + begin);
-    const int n4 = (end - begin) >> 2;
-    for (int i = threadIdx.x; i < n4; i += 4 * kStatsThreads) {
-      float4 v0 = stream_load4(p + i);
-      float4 v1 = (i + kStatsThreads < n4) ? stream_load4(p + i + kStatsThreads) : neg;
-      float4 v2 = (i + 2 * kStatsThreads < n4) ? stream_load4(p + i + 2 * kStatsThreads) : neg;
-      float4 v3 = (i + 3 * kStatsThreads < n4) ? stream_load4(p + i + 3 * kStatsThreads) : neg;
-      float bm = fmaxf(fmaxf(max4(v0), max4(v1)), fmaxf(max4(v2), max4(v3)));
+    const T* p = base + begin;
+    const int n_pk = (end - begin) / W;
+    for (int i = threadIdx.x; i < n_pk; i += 4 * kStatsThreads) {
+      float v0[W], v1[W], v2[W], v3[W];
+#pragma unroll
+      for (int k = 0; k < W; ++k) v1[k] = v2[k] = v3[k] = -INFINITY;
+      Pack<T>::template load<true>(p + (size_t)i * W, v0);
+      if (i + kStatsThreads < n_pk) Pack<T>::template load<true>(p + (size_t)(i + kStatsThreads) * W, v1);
+      if (i + 2 * kStatsThreads < n_pk) Pack<T>::template load<true>(p + (size_t)(i + 2 * kStatsThreads) * W, v2);
+      if (i + 3 * kStatsThreads < n_pk) Pack<T>::template load<true>(p + (size_t)(i + 3 * kStatsThreads) * W, v3);
+      const float bm = fmaxf(fmaxf(max_of<W>(v0), max_of<W>(v1)), fmaxf(max_of<W>(v2), max_of<W>(v3)));
       if (bm > m) {
         s *= __expf(m - bm);     // m = -inf gives exp(-inf) = 0 and s is 0 anyway
         m = bm;
       }
       const float mm = (m == -INFINITY) ? 0.f : m;   // a lane that has seen only -inf adds exp(-inf) = 0
-      float a0 = __expf(v0.x - mm) + __expf(v0.y - mm) + __expf(v0.z - mm) + __expf(v0.w - mm);
-      float a1 = __expf(v1.x - mm) + __expf(v1.y - mm) + __expf(v1.z - mm) + __expf(v1.w - mm);
-      float a2 = __expf(v2.x - mm) + __expf(v2.y - mm) + __expf(v2.z - mm) + __expf(v2.w - mm);
-      float a3 = __expf(v3.x - mm) + __expf(v3.y - mm) + __expf(v3.z - mm) + __expf(v3.w - mm);
+      const float a0 = sum_exp_of<W>(v0, mm), a1 = sum_exp_of<W>(v1, mm);
+      const float a2 = sum_exp_of<W>(v2, mm), a3 = sum_exp_of<W>(v3, mm);
       s += (a0 + a1) + (a2 + a3);
     }
   } else {
     for (int i = begin + threadIdx.x; i < end; i += kStatsThreads) {
-      float v = base[i];
+      const float v = Storage<T>::load(base + i);
       if (v > m) {
         s *= __expf(m - v);
         m = v;
@@ -119,6 +153,24 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const float* _
   }
 }
 
+// merge_stats: the statistics of a row from the per-column-block pairs that the LM-head projection left
+// (stats [rows][n_blocks]).  grid rows, one wavefront: lanes stride over the blocks, then a fixed-order merge.
+__global__ __launch_bounds__(64) void merge_stats_kernel(const float2* __restrict__ stats, int n_blocks,
+                                                         float2* __restrict__ row_stat) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  const float2* p = stats + (size_t)row * n_blocks;
+  float m = -INFINITY, s = 0.f;
+  for (int b = lane; b < n_blocks; b += 64) {
+    const float2 v = p[b];
+    merge_pair(m, s, v.x, v.y);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    const float m2 = __shfl_down(m, off), s2 = __shfl_down(s, off);
+    merge_pair(m, s, m2, s2);
+  }
+  if (lane == 0) row_stat[row] = make_float2(m, s);
+}
+
 // Weight of token t in the draw: max(0, p - q) or p.
 __device__ __forceinline__ float draw_weight(float logit, float q, float row_max, float inv_z, bool residual) {
   float p = expf(logit - row_max) * inv_z;
@@ -126,30 +178,39 @@ __device__ __forceinline__ float draw_weight(float logit, float q, float row_max
 }
 
 // Loads this lane's 8 consecutive weights of a tile; tokens >= vocab weigh 0.
-template <bool VEC>
-__device__ __forceinline__ void load_weights8(const float* __restrict__ lrow, const float* __restrict__ qrow, int t0,
+template <typename T, bool VEC>
+__device__ __forceinline__ void load_weights8(const T* __restrict__ lrow, const T* __restrict__ qrow, int t0,
                                               int vocab, float row_max, float inv_z, bool residual, float w[8]) {
   if (VEC && t0 + 8 <= vocab) {
-    const float4 l0 = *reinterpret_cast<const float4*>(lrow + t0);
-    const float4 l1 = *reinterpret_cast<const float4*>(lrow + t0 + 4);
-    float4 q0 = make_float4(0, 0, 0, 0), q1 = q0;
-    if (residual) {
-      q0 = *reinterpret_cast<const float4*>(qrow + t0);
-      q1 = *reinterpret_cast<const float4*>(qrow + t0 + 4);
+    constexpr int W = Pack<T>::W;
+    float l[8], q[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) q[k] = 0.f;
+#pragma unroll
+    for (int h = 0; h < 8 / W; ++h) {
+      float part[W];
+      Pack<T>::template load<false>(lrow + t0 + h * W, part);
+#pragma unroll
+      for (int k = 0; k < W; ++k) l[h * W + k] = part[k];
     }
-    w[0] = draw_weight(l0.x, q0.x, row_max, inv_z, residual);
-    w[1] = draw_weight(l0.y, q0.y, row_max, inv_z, residual);
-    w[2] = draw_weight(l0.z, q0.z, row_max, inv_z, residual);
-    w[3] = draw_weight(l0.w, q0.w, row_max, inv_z, residual);
-    w[4] = draw_weight(l1.x, q1.x, row_max, inv_z, residual);
-    w[5] = draw_weight(l1.y, q1.y, row_max, inv_z, residual);
-    w[6] = draw_weight(l1.z, q1.z, row_max, inv_z, residual);
-    w[7] = draw_weight(l1.w, q1.w, row_max, inv_z, residual);
+    if (residual) {
+#pragma unroll
+      for (int h = 0; h < 8 / W; ++h) {
+        float part[W];
+        Pack<T>::template load<false>(qrow + t0 + h * W, part);
+#pragma unroll
+        for (int k = 0; k < W; ++k) q[h * W + k] = part[k];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = draw_weight(l[k], q[k], row_max, inv_z, residual);
   } else {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int t = t0 + k;
-      w[k] = (t < vocab) ? draw_weight(lrow[t], residual ? qrow[t] : 0.f, row_max, inv_z, residual) : 0.f;
+      w[k] = (t < vocab) ? draw_weight(Storage<T>::load(lrow + t), residual ? Storage<T>::load(qrow + t) : 0.f, row_max,
+                                       inv_z, residual)
+                         : 0.f;
     }
   }
 }
@@ -196,9 +257,10 @@ __device__ __forceinline__ void row_max_sum(const float2* __restrict__ partial, 
 
 // The accept decisions of one server, computed by one wavefront (lanes over draft positions).
 // Returns the decision in every lane; lane 0 of a workgroup with write_out set stores the outputs.
+template <typename T>
 __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict__ cu_rows, int vocab, int n_chunks,
                                                   const float2* __restrict__ partial,
-                                                  const float* __restrict__ logits, const float* __restrict__ q_probs,
+                                                  const T* __restrict__ logits, const T* __restrict__ q_probs,
                                                   const int* __restrict__ draft_tokens,
                                                   const float* __restrict__ u_accept, bool write_out,
                                                   int* __restrict__ accepted_len, float* __restrict__ accept_stat,
@@ -218,8 +280,8 @@ __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict
       tok = 0;
     }
     const float u = u_accept[d0 + j];
-    const float lg = logits[(size_t)row * vocab + tok];
-    const float q = q_probs[(size_t)(d0 + j) * vocab + tok];
+    const float lg = Storage<T>::load(logits + (size_t)row * vocab + tok);
+    const float q = Storage<T>::load(q_probs + (size_t)(d0 + j) * vocab + tok);
     float m, s;
     row_max_sum(partial, row, n_chunks, m, s);
     const float p = expf(lg - m) / s;
@@ -254,12 +316,12 @@ __device__ __forceinline__ Decision decide_server(int srv, const int* __restrict
 // ---------------------------------------------------------------------------------------
 constexpr int kTilesPerGroup = 4;
 
-template <bool VEC>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __restrict__ cu_rows, int vocab,
                                                                   int n_chunks, int n_tiles, int n_groups,
                                                                   const float2* __restrict__ partial,
-                                                                  const float* __restrict__ logits,
-                                                                  const float* __restrict__ q_probs,
+                                                                  const T* __restrict__ logits,
+                                                                  const T* __restrict__ q_probs,
                                                                   const int* __restrict__ draft_tokens,
                                                                   const float* __restrict__ u_accept,
                                                                   int* __restrict__ accepted_len,
@@ -271,7 +333,7 @@ __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __r
   __shared__ Decision sh_d;
   __shared__ double part[kTileThreads / 64];
   if (threadIdx.x < 64) {
-    const Decision dd = decide_server(srv, cu_rows, vocab, n_chunks, partial, logits, q_probs, draft_tokens, u_accept,
+    const Decision dd = decide_server<T>(srv, cu_rows, vocab, n_chunks, partial, logits, q_probs, draft_tokens, u_accept,
                                       group == 0, accepted_len, accept_stat, ratio_out);
     if (threadIdx.x == 0) {
       sh_d = dd;
@@ -281,15 +343,15 @@ __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __r
   __syncthreads();
   const Decision d = sh_d;
   const bool residual = d.q_row >= 0;
-  const float* lrow = logits + (size_t)d.row * vocab;
-  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
+  const T* lrow = logits + (size_t)d.row * vocab;
+  const T* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
   // all loads of the group's tiles are issued before the first is consumed
   float w[kTilesPerGroup][8];
 #pragma unroll
   for (int k = 0; k < kTilesPerGroup; ++k) {
     const int tile = group * kTilesPerGroup + k;
     if (tile < n_tiles)
-      load_weights8<VEC>(lrow, qrow, tile * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, residual, w[k]);
+      load_weights8<T, VEC>(lrow, qrow, tile * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, residual, w[k]);
   }
 #pragma unroll
   for (int k = 0; k < kTilesPerGroup; ++k) {
@@ -311,18 +373,18 @@ __global__ __launch_bounds__(kTileThreads) void draw_tiles_kernel(const int* __r
 // ---------------------------------------------------------------------------------------
 // pick_token: one workgroup per server.
 // ---------------------------------------------------------------------------------------
-template <bool VEC>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision* __restrict__ decision, int vocab,
-                                                                   int n_tiles, const float* __restrict__ logits,
-                                                                   const float* __restrict__ q_probs,
+                                                                   int n_tiles, const T* __restrict__ logits,
+                                                                   const T* __restrict__ q_probs,
                                                                    const double* __restrict__ tile_sums,
                                                                    const float* __restrict__ u_resample,
                                                                    int* __restrict__ next_token) {
   const int srv = blockIdx.x;
   const Decision d = decision[srv];
   bool residual = d.q_row >= 0;
-  const float* lrow = logits + (size_t)d.row * vocab;
-  const float* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
+  const T* lrow = logits + (size_t)d.row * vocab;
+  const T* qrow = residual ? q_probs + (size_t)d.q_row * vocab : nullptr;
   __shared__ double wave_tot[kTileThreads / 64];
   __shared__ double sh_prefix;
   __shared__ int sh_tile, sh_found, sh_last_pos;
@@ -347,7 +409,7 @@ __global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision
     // recompute the total of p tile by tile (rare path, one workgroup walks the row)
     double tot = 0.0;
     for (int t = 0; t < n_tiles; ++t) {
-      load_weights8<VEC>(lrow, nullptr, t * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, false, w);
+      load_weights8<T, VEC>(lrow, nullptr, t * kTileElems + threadIdx.x * 8, vocab, d.row_max, d.inv_z, false, w);
       double ex;
       double incl = block_scan((double)sum8(w), wave_tot, ex);
       if (threadIdx.x == kTileThreads - 1) sh_prefix = incl;
@@ -417,7 +479,7 @@ __global__ __launch_bounds__(kTileThreads) void pick_token_kernel(const Decision
   int last_pos_any = -1;
   for (;;) {
     const int t0 = tile * kTileElems + threadIdx.x * 8;
-    load_weights8<VEC>(lrow, qrow, t0, vocab, d.row_max, d.inv_z, residual, w);
+    load_weights8<T, VEC>(lrow, qrow, t0, vocab, d.row_max, d.inv_z, residual, w);
     double excl;
     const double incl = block_scan((double)sum8(w), wave_tot, excl);
     // exactly one lane sees the running sum cross the target inside its 8 tokens
@@ -470,10 +532,11 @@ struct AcceptPlan {
   double* tile_sums;
 };
 
-AcceptPlan plan_accept(int n_servers, int n_rows, int vocab, void* workspace) {
+// pack: elements per 16-byte load of the element type (4 for fp32, 8 for bf16); a chunk is a whole number of them
+AcceptPlan plan_accept(int n_servers, int n_rows, int vocab, void* workspace, int pack = 4) {
   AcceptPlan p;
   p.n_chunks = pick_chunks(n_rows, vocab);
-  p.chunk_len = (ceil_div(vocab, p.n_chunks) + 3) / 4 * 4;
+  p.chunk_len = (ceil_div(vocab, p.n_chunks) + pack - 1) / pack * pack;
   p.n_chunks = ceil_div(vocab, p.chunk_len);
   p.n_tiles = ceil_div(vocab, kTileElems);
   Carver c(workspace);
@@ -484,46 +547,61 @@ AcceptPlan plan_accept(int n_servers, int n_rows, int vocab, void* workspace) {
   return p;
 }
 
-}  // namespace
-
-// Enqueues the kernels; arguments already validated.  n_rows = sum(gamma + 1).
-gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
-                        const float* q_probs, const int* draft_tokens, const float* u_accept,
-                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream) {
-  AcceptPlan p = plan_accept(n_servers, n_rows, vocab, workspace);
-  const bool vec = (vocab % 4 == 0) && (reinterpret_cast<uintptr_t>(target_logits) % 16 == 0) &&
-                   (q_probs == nullptr || reinterpret_cast<uintptr_t>(q_probs) % 16 == 0);
-  const unsigned g1 = (unsigned)p.n_chunks * (unsigned)n_rows;
-  if (vec)
-    row_stats_kernel<true><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.n_chunks, p.partial);
-  else
-    row_stats_kernel<false><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.n_chunks, p.partial);
-  GS_LAUNCH_CHECK("row_stats");
+template <typename T, bool VEC>
+gs_status launch_accept_t(const AcceptPlan& p, int n_servers, int n_rows, const int* cu_rows, int vocab,
+                          const T* target_logits, const T* q_probs, const int* draft_tokens, const float* u_accept,
+                          const float* u_resample, const gs_accept_out* out, hipStream_t stream,
+                          const void* row_stats, int n_stat_blocks) {
+  int n_chunks = p.n_chunks;
+  if (row_stats) {      // one pair per row, merged from the producer's column-block pairs
+    merge_stats_kernel<<<n_rows, 64, 0, stream>>>(static_cast<const float2*>(row_stats), n_stat_blocks, p.partial);
+    GS_LAUNCH_CHECK("merge_stats");
+    n_chunks = 1;
+  } else {
+    const unsigned g1 = (unsigned)p.n_chunks * (unsigned)n_rows;
+    row_stats_kernel<T, VEC><<<g1, kStatsThreads, 0, stream>>>(target_logits, vocab, p.chunk_len, p.n_chunks, p.partial);
+    GS_LAUNCH_CHECK("row_stats");
+  }
   const int n_groups = ceil_div(p.n_tiles, kTilesPerGroup);
   const unsigned g2 = (unsigned)n_groups * (unsigned)n_servers;
-  if (vec) {
-    draw_tiles_kernel<true><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, n_groups, p.partial,
+  draw_tiles_kernel<T, VEC><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, n_chunks, p.n_tiles, n_groups, p.partial,
                                                              target_logits, q_probs, draft_tokens, u_accept,
                                                              out->accepted_len, out->accept_stat, out->ratio,
                                                              p.decision, p.tile_sums);
-    GS_LAUNCH_CHECK("draw_tiles");
-    pick_token_kernel<true><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
-                                                                    q_probs, p.tile_sums, u_resample, out->next_token);
-  } else {
-    draw_tiles_kernel<false><<<g2, kTileThreads, 0, stream>>>(cu_rows, vocab, p.n_chunks, p.n_tiles, n_groups, p.partial,
-                                                              target_logits, q_probs, draft_tokens, u_accept,
-                                                              out->accepted_len, out->accept_stat, out->ratio,
-                                                              p.decision, p.tile_sums);
-    GS_LAUNCH_CHECK("draw_tiles");
-    pick_token_kernel<false><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits,
-                                                                     q_probs, p.tile_sums, u_resample, out->next_token);
-  }
+  GS_LAUNCH_CHECK("draw_tiles");
+  pick_token_kernel<T, VEC><<<n_servers, kTileThreads, 0, stream>>>(p.decision, vocab, p.n_tiles, target_logits, q_probs,
+                                                                    p.tile_sums, u_resample, out->next_token);
   GS_LAUNCH_CHECK("pick_token");
   return GS_OK;
 }
 
+}  // namespace
+
+// Enqueues the kernels; arguments already validated.  n_rows = sum(gamma + 1).
+// elem: GS_F32 or GS_BF16, the type of target_logits and q_probs.
+// row_stats: [n_rows][n_stat_blocks] pairs (max, sum exp) that the producer of the logits already reduced, or
+// null: then the logits are read once more for them.
+gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, int elem, const void* target_logits,
+                        const void* q_probs, const int* draft_tokens, const float* u_accept,
+                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream,
+                        const void* row_stats, int n_stat_blocks) {
+  const int pack = elem == GS_BF16 ? 8 : 4;
+  const AcceptPlan p = plan_accept(n_servers, n_rows, vocab, workspace, pack);
+  const bool vec = (vocab % pack == 0) && (reinterpret_cast<uintptr_t>(target_logits) % 16 == 0) &&
+                   (q_probs == nullptr || reinterpret_cast<uintptr_t>(q_probs) % 16 == 0);
+#define GS_ACCEPT(T_, VEC_)                                                                                        \
+  launch_accept_t<T_, VEC_>(p, n_servers, n_rows, cu_rows, vocab, static_cast<const T_*>(target_logits),           \
+                            static_cast<const T_*>(q_probs), draft_tokens, u_accept, u_resample, out, stream,      \
+                            row_stats, n_stat_blocks)
+  if (elem == GS_BF16) return vec ? GS_ACCEPT(bf16_t, true) : GS_ACCEPT(bf16_t, false);
+  return vec ? GS_ACCEPT(float, true) : GS_ACCEPT(float, false);
+#undef GS_ACCEPT
+}
+
 size_t accept_workspace_bytes(int n_servers, int n_rows, int vocab) {
-  return plan_accept(n_servers, n_rows, vocab, nullptr).bytes;
+  const size_t a = plan_accept(n_servers, n_rows, vocab, nullptr, 4).bytes;
+  const size_t b = plan_accept(n_servers, n_rows, vocab, nullptr, 8).bytes;
+  return a > b ? a : b;
 }
 
 }  // namespace gs
@@ -533,28 +611,50 @@ extern "C" size_t gs_accept_workspace_bytes(int n_servers, int n_rows, int vocab
   return gs::accept_workspace_bytes(n_servers, n_rows, vocab);
 }
 
+namespace gs {
+namespace {
+
+gs_status accept_entry(int elem, int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                       const void* target_logits, const void* q_probs, const int* draft_tokens,
+                       const float* u_accept, const float* u_resample, const gs_accept_out* out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  if (n_servers <= 0 || vocab <= 0) return fail(GS_EINVAL, "n_servers and vocab must be positive");
+  if (!gamma_host || !cu_rows || !target_logits || !u_resample || !out || !workspace)
+    return fail(GS_EINVAL, "null argument");
+  if (!out->accepted_len || !out->next_token || !out->accept_stat)
+    return fail(GS_EINVAL, "accepted_len, next_token and accept_stat outputs are required");
+  long n_rows = 0, n_draft = 0;
+  for (int i = 0; i < n_servers; ++i) {
+    if (gamma_host[i] < 0) return fail(GS_EINVAL, "gamma[%d] = %d is negative", i, gamma_host[i]);
+    n_rows += gamma_host[i] + 1;
+    n_draft += gamma_host[i];
+  }
+  if (n_rows > kMaxAcceptRows) return fail(GS_EINVAL, "too many rows (at most %ld)", kMaxAcceptRows);
+  if (n_draft > 0 && (!q_probs || !draft_tokens || !u_accept))
+    return fail(GS_EINVAL, "q_probs, draft_tokens and u_accept are required when any gamma > 0");
+  if (workspace_bytes < accept_workspace_bytes(n_servers, (int)n_rows, vocab))
+    return fail(GS_ECAPACITY, "workspace of %zu bytes is smaller than gs_accept_workspace_bytes", workspace_bytes);
+  return launch_accept(n_servers, (int)n_rows, cu_rows, vocab, elem, target_logits, q_probs, draft_tokens, u_accept,
+                       u_resample, out, workspace, static_cast<hipStream_t>(hip_stream), nullptr, 0);
+}
+
+}  // namespace
+}  // namespace gs
+
 extern "C" gs_status gs_accept_reject(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
                                       const float* target_logits, const float* q_probs, const int* draft_tokens,
                                       const float* u_accept, const float* u_resample, const gs_accept_out* out,
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (n_servers <= 0 || vocab <= 0) return gs::fail(GS_EINVAL, "n_servers and vocab must be positive");
-  if (!gamma_host || !cu_rows || !target_logits || !u_resample || !out || !workspace)
-    return gs::fail(GS_EINVAL, "null argument");
-  if (!out->accepted_len || !out->next_token || !out->accept_stat)
-    return gs::fail(GS_EINVAL, "accepted_len, next_token and accept_stat outputs are required");
-  long n_rows = 0, n_draft = 0;
-  for (int i = 0; i < n_servers; ++i) {
-    if (gamma_host[i] < 0) return gs::fail(GS_EINVAL, "gamma[%d] = %d is negative", i, gamma_host[i]);
-    n_rows += gamma_host[i] + 1;
-    n_draft += gamma_host[i];
-  }
-  if (n_rows > gs::kMaxAcceptRows) return gs::fail(GS_EINVAL, "too many rows (at most %ld)", gs::kMaxAcceptRows);
-  if (n_draft > 0 && (!q_probs || !draft_tokens || !u_accept))
-    return gs::fail(GS_EINVAL, "q_probs, draft_tokens and u_accept are required when any gamma > 0");
-  if (workspace_bytes < gs::accept_workspace_bytes(n_servers, (int)n_rows, vocab))
-    return gs::fail(GS_ECAPACITY, "workspace of %zu bytes is smaller than gs_accept_workspace_bytes", workspace_bytes);
-  return gs::launch_accept(n_servers, (int)n_rows, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept,
-                           u_resample, out, workspace, static_cast<hipStream_t>(hip_stream));
+  return gs::accept_entry(GS_F32, n_servers, gamma_host, cu_rows, vocab, target_logits, q_probs, draft_tokens, u_accept,
+                          u_resample, out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" gs_status gs_accept_reject_bf16(int n_servers, const int* gamma_host, const int* cu_rows, int vocab,
+                                           const void* target_logits, const void* q_probs, const int* draft_tokens,
+                                           const float* u_accept, const float* u_resample, const gs_accept_out* out,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return gs::accept_entry(GS_BF16, n_servers, gamma_host, cu_rows, vocab, target_logits, q_probs, draft_tokens,
+                          u_accept, u_resample, out, workspace, workspace_bytes, hip_stream);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -43,11 +43,23 @@ constexpr int kTargetWorkgroups = 512;   // about two per CU
 constexpr int kBK = 64;           // k elements per step
 constexpr int kLdsRow = kBK + 8;  // padded LDS row (bf16 elements): 144 bytes
 
-template <int MT, int DEPTH, int NW>
+// Merge of two online-softmax pairs (max, sum exp(x - max)).
+__device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s2) {
+  const float M = fmaxf(m, m2);
+  s = s * __expf(m - M) + s2 * __expf(m2 - M);
+  m = M;
+}
+
+// STATS (LM head, one K split): the epilogue also reduces every output row over the workgroup's columns to the
+// pair (max, sum exp(y - max)) and stores it at stats[row][column block], so that the vocabulary softmax
+// statistics (Section II-A-1) come out of the projection and the logits need not be read again for them.
+template <int MT, int DEPTH, int NW, bool STATS = false>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t* __restrict__ X,
                                                                    const bf16_t* __restrict__ Wp,
                                                                    float* __restrict__ P, int M, int N, int K,
-                                                                   int k_per_split, int m_chunks) {
+                                                                   int k_per_split, int m_chunks,
+                                                                   float2* __restrict__ stats = nullptr,
+                                                                   int n_stat_blocks = 0) {
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
@@ -156,6 +168,30 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
     for (int i = 0; i < 4; ++i) {
       const int row = m0 + mt * 16 + g * 4 + i;
       if (row < M) out[(size_t)row * N + n0 + c] = acc[mt][i];
+    }
+  }
+  if constexpr (STATS) {
+    // lanes (g, 0..15) hold the 16 columns of row mt*16 + g*4 + i: reduce over c, then over the waves
+    __shared__ float2 st[NW][MT * 16];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = acc[mt][i];
+        float mx = v;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        float e = __expf(v - mx);
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) e += __shfl_xor(e, off);
+        if (c == 0) st[wave][mt * 16 + g * 4 + i] = make_float2(mx, e);
+      }
+    __syncthreads();
+    if (tid < MT * 16 && m0 + tid < M) {
+      float m = st[0][tid].x, sum = st[0][tid].y;
+#pragma unroll
+      for (int w = 1; w < NW; ++w) merge_stat(m, sum, st[w][tid].x, st[w][tid].y);
+      stats[(size_t)(m0 + tid) * n_stat_blocks + n_block] = make_float2(m, sum);
     }
   }
 }
@@ -270,11 +306,14 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_gate_up_kernel(const bf16_t
 // GATE_UP (NT = 2, one K split): the wave's two column tiles are feature tile t of the gate half and of the
 // up half of a [2F][K] matrix, and the epilogue stores act[r][f] = silu(gate) * up as bf16 ([M][N/2], at P)
 // instead of the fp32 sums.
-template <int MT, int NT, int DEPTH, bool GATE_UP = false>
+// STATS: as in the skinny kernel, (max, sum exp) of every row over the workgroup's 64 NT columns.
+template <int MT, int NT, int DEPTH, bool GATE_UP = false, bool STATS = false>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __restrict__ X,
                                                                 const bf16_t* __restrict__ Wp,
                                                                 float* __restrict__ P, int M, int N, int K,
-                                                                int k_per_split, int m_chunks) {
+                                                                int k_per_split, int m_chunks,
+                                                                float2* __restrict__ stats = nullptr,
+                                                                int n_stat_blocks = 0) {
   static_assert(!GATE_UP || NT % 2 == 0, "gate and up tile of every feature tile");
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -398,6 +437,33 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
         for (int nt = 0; nt < NT; ++nt) out[(size_t)row * N + (n_tile0 + nt) * 16 + c] = acc[mt][nt][i];
       }
     }
+  if constexpr (STATS) {
+    __shared__ float2 st[4][MT * 16];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float mx = acc[mt][0][i];
+#pragma unroll
+        for (int nt = 1; nt < NT; ++nt) mx = fmaxf(mx, acc[mt][nt][i]);
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        float e = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) e += __expf(acc[mt][nt][i] - mx);
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) e += __shfl_xor(e, off);
+        if (c == 0) st[wave][mt * 16 + g * 4 + i] = make_float2(mx, e);
+      }
+    __syncthreads();
+    for (int r = tid; r < MT * 16; r += 256)
+      if (m0 + r < M) {
+        float m = st[0][r].x, sum = st[0][r].y;
+#pragma unroll
+        for (int w = 1; w < 4; ++w) merge_stat(m, sum, st[w][r].x, st[w][r].y);
+        stats[(size_t)(m0 + r) * n_stat_blocks + n_block] = make_float2(m, sum);
+      }
+  }
 }
 
 // fp32: 64x64 output tile, k step 16, each of 256 threads owns a 4x4 block.
@@ -600,6 +666,58 @@ gs_status launch_gemm_gate_up(const void* X, const void* W, void* act, int M, in
   else if (tiles <= 2) gemm_bf16_gate_up_kernel<2, D, NW><<<grid, 64 * NW, 0, stream>>>(x, w, a, M, F, K);
   else gemm_bf16_gate_up_kernel<4, D, NW><<<grid, 64 * NW, 0, stream>>>(x, w, a, M, F, K);
   GS_LAUNCH_CHECK("gemm_gate_up");
+  return GS_OK;
+}
+
+// Number of column blocks per row of the statistics that launch_gemm_stats writes for this shape, or 0 where
+// the projection of this shape does not emit them (fp32 and 4-bit models, shapes that need a K split).
+int gemm_stat_blocks(int dtype, int M, int N, int K) {
+  if (dtype != GS_BF16 || M <= 0) return 0;
+  const GemmPlan p = gemm_plan(M, N, K);
+  if (p.splits != 1) return 0;
+  return p.tall ? N / (64 * p.nt) : N / (16 * p.waves);
+}
+
+// Y [M][N] = X W^T (one K split) and stats [M][gemm_stat_blocks] = per row and column block (max, sum exp(y - max)).
+gs_status launch_gemm_stats(const void* X, const void* W, float* Y, void* stats, int M, int N, int K,
+                            hipStream_t stream) {
+  const GemmPlan p = gemm_plan(M, N, K);
+  const bf16_t* x = static_cast<const bf16_t*>(X);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  float2* st = static_cast<float2*>(stats);
+  const int nb = gemm_stat_blocks(GS_BF16, M, N, K);
+  if (nb == 0) return fail(GS_EUNSUPPORTED, "this projection shape does not emit softmax statistics");
+  if (p.tall) {
+    const dim3 grid(ceil_div(N / (64 * p.nt), 8) * 8 * p.m_chunks, 1, 1);
+    if (p.nt == 4) gemm_bf16_tall_kernel<8, 4, 1, false, true><<<grid, 256, 0, stream>>>(x, w, Y, M, N, K, p.k_per, p.m_chunks, st, nb);
+    else if (p.mt == 6) gemm_bf16_tall_kernel<6, 2, 2, false, true><<<grid, 256, 0, stream>>>(x, w, Y, M, N, K, p.k_per, p.m_chunks, st, nb);
+    else if (p.mt == 8) gemm_bf16_tall_kernel<8, 2, 2, false, true><<<grid, 256, 0, stream>>>(x, w, Y, M, N, K, p.k_per, p.m_chunks, st, nb);
+    else gemm_bf16_tall_kernel<10, 2, 2, false, true><<<grid, 256, 0, stream>>>(x, w, Y, M, N, K, p.k_per, p.m_chunks, st, nb);
+  } else {
+    const int n_blocks = N / (16 * p.waves);
+    const int gx = p.m_chunks > 1 ? ceil_div(n_blocks, 8) * 8 * p.m_chunks : n_blocks;
+    const dim3 grid(gx, 1, 1);
+    const int mc = p.mt == 8 ? p.m_chunks : 1;
+#define GS_SKINNY_STATS(MT_, NW_) \
+  gemm_bf16_skinny_kernel<MT_, kSkinnyDepth, NW_, true><<<grid, 64 * NW_, 0, stream>>>(x, w, Y, M, N, K, p.k_per, mc, st, nb)
+    if (p.waves == 8) {
+      switch (p.mt) {
+        case 1: GS_SKINNY_STATS(1, 8); break;
+        case 2: GS_SKINNY_STATS(2, 8); break;
+        case 4: GS_SKINNY_STATS(4, 8); break;
+        default: GS_SKINNY_STATS(8, 8);
+      }
+    } else {
+      switch (p.mt) {
+        case 1: GS_SKINNY_STATS(1, 4); break;
+        case 2: GS_SKINNY_STATS(2, 4); break;
+        case 4: GS_SKINNY_STATS(4, 4); break;
+        default: GS_SKINNY_STATS(8, 4);
+      }
+    }
+#undef GS_SKINNY_STATS
+  }
+  GS_LAUNCH_CHECK("gemm_bf16_stats");
   return GS_OK;
 }
 

@@ -41,9 +41,13 @@ size_t attention_work_ints(int capacity);
 gs_status launch_attention_work(const int* cu_rows, const int* ctx_len, int n_servers, const int* block_table,
                                 int max_blocks, int page_size, int steps_per_split, int capacity, int* work,
                                 hipStream_t stream);
-gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, const float* target_logits,
-                        const float* q_probs, const int* draft_tokens, const float* u_accept,
-                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream);
+gs_status launch_accept(int n_servers, int n_rows, const int* cu_rows, int vocab, int elem, const void* target_logits,
+                        const void* q_probs, const int* draft_tokens, const float* u_accept,
+                        const float* u_resample, const gs_accept_out* out, void* workspace, hipStream_t stream,
+                        const void* row_stats, int n_stat_blocks);
+int gemm_stat_blocks(int dtype, int M, int N, int K);
+gs_status launch_gemm_stats(const void* X, const void* W, float* Y, void* stats, int M, int N, int K,
+                            hipStream_t stream);
 size_t accept_workspace_bytes(int n_servers, int n_rows, int vocab);
 
 }  // namespace gs
@@ -84,6 +88,7 @@ struct Plan {
   int* attn_work;   // the step's (server, split) work list of the attention kernel
   int attn_work_capacity;
   void* accept_ws;
+  void* lm_stats;   // [R][column blocks] (max, sum exp) pairs from the LM-head projection's epilogue
   size_t bytes;
 };
 
@@ -133,6 +138,7 @@ Plan make_plan(const gs_ctx* ctx, int max_rows, int max_servers, int max_ctx, vo
   size_t acc = 0;
   for (int n = 1; n <= max_servers; ++n) acc = std::max(acc, gs::accept_workspace_bytes(n, max_rows, m.vocab));
   p.accept_ws = c.take<char>(acc);
+  p.lm_stats = c.take<float>(2 * R * (size_t)(m.vocab / 64 + 1));     // at least 64 columns per block
   p.bytes = c.used();
   return p;
 }
@@ -448,7 +454,12 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
                                 hipMemcpyDeviceToDevice, stream));
   float* logits = logits_out ? logits_out : p.logits;
   const int lm_splits = gs::gemm_splits(m.dtype, rows, m.vocab, d);
-  if (lm_splits == 1) {
+  // Where the LM-head projection runs as one bf16 launch, its epilogue also leaves the softmax statistics of
+  // every row per column block, and the accept stage does not read the logits again for them.
+  const int stat_blocks = do_accept ? gs::gemm_stat_blocks(m.dtype, rows, m.vocab, d) : 0;
+  if (stat_blocks > 0) {
+    GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm_stats(p.h, ctx->lm_head, logits, p.lm_stats, rows, m.vocab, d, stream));
+  } else if (lm_splits == 1) {
     GS_STAGE(GS_STAGE_GEMM, gs::launch_gemm(m.dtype, p.h, ctx->lm_head, logits, rows, m.vocab, d, stream));
   } else {   // small vocabularies only: the partials fit the projection scratch
     GS_TRY(gs::launch_gemm(m.dtype, p.h, ctx->lm_head, p.partial, rows, m.vocab, d, stream));
@@ -461,8 +472,9 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
       gather_draft_tokens_kernel<<<n, 64, 0, stream>>>(b->tokens, b->cu_rows, n, p.draft_tokens);
       GS_LAUNCH_CHECK("gather_draft_tokens");
     }
-    GS_STAGE(GS_STAGE_ACCEPT, gs::launch_accept(n, rows, b->cu_rows, m.vocab, logits, b->q_probs, p.draft_tokens,
-                                                b->u_accept, b->u_resample, out, p.accept_ws, stream));
+    GS_STAGE(GS_STAGE_ACCEPT, gs::launch_accept(n, rows, b->cu_rows, m.vocab, GS_F32, logits, b->q_probs, p.draft_tokens,
+                                                b->u_accept, b->u_resample, out, p.accept_ws, stream,
+                                                stat_blocks > 0 ? p.lm_stats : nullptr, stat_blocks));
   }
 #undef GS_STAGE
 #undef GS_TRY

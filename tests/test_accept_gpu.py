@@ -9,10 +9,19 @@ from tests.parity import check_accept_outputs
 pytestmark = pytest.mark.gpu
 
 
-def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0, pinned_out=False):
+def _as_bf16(inp: synth.AcceptInputs):
+    """The same inputs with target logits and q rounded to bfloat16 (held in float32 arrays): what a caller of the
+    bfloat16 entry point hands over, and what the oracle is given."""
+    import dataclasses
+    return dataclasses.replace(inp, target_logits=synth.round_to_bf16(inp.target_logits),
+                               q_probs=synth.round_to_bf16(inp.q_probs))
+
+
+def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0, pinned_out=False, bf16=False):
     import torch
     from paper_2512_09963_amd import binding as gsb
     dev = torch.device("cuda:0")
+    wide = torch.bfloat16 if bf16 else torch.float32
     n = inp.gamma.size
     R, G, V = inp.target_logits.shape[0], inp.q_probs.shape[0], inp.vocab
 
@@ -25,7 +34,7 @@ def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0, pinned_ou
             return view
         return t.to(dev)
 
-    tl, q = up(inp.target_logits, torch.float32), up(inp.q_probs, torch.float32) if G else None
+    tl, q = up(inp.target_logits, wide), up(inp.q_probs, wide) if G else None
     toks = up(inp.draft_tokens, torch.int32) if G else None
     ua = up(inp.u_accept, torch.float32) if G else None
     ur = up(inp.u_resample, torch.float32)
@@ -37,7 +46,7 @@ def _run_gpu(inp: synth.AcceptInputs, want_ratio=True, offset_elems=0, pinned_ou
     for k in ("accepted_len", "next_token"):
         out[k].fill_(-7)
     ws = torch.empty(gsb.gs_accept_workspace_bytes(n, R, V), dtype=torch.uint8, device=dev)
-    gsb.gs_accept_reject(inp.gamma, cu, V, tl, q, toks, ua, ur, out, ws)
+    (gsb.gs_accept_reject_bf16 if bf16 else gsb.gs_accept_reject)(inp.gamma, cu, V, tl, q, toks, ua, ur, out, ws)
     torch.cuda.synchronize()
     return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
 
@@ -144,4 +153,41 @@ def test_config2_full_size(sigma):
     bands = _check(inp, got)
     rate = got["accepted_len"].mean() / 8
     print(f"sigma={sigma}: mean accepted/gamma = {rate:.3f}, bands = {bands}")
+    assert bands["n_band_m"] + bands["n_band_tok"] <= 2
+
+
+@pytest.mark.parametrize("vocab,offset", [(1024, 0), (6152, 0), (5003, 0), (6152, 1), (6152, 8), (40000, 0)])
+@pytest.mark.parametrize("sigma", [0.3, 1.5])
+def test_bf16_inputs_small_ragged_batches(vocab, offset, sigma):
+    """gs_accept_reject_bf16: the oracle gets the same bfloat16 numbers (widened), so the bar is unchanged."""
+    gamma = np.array([2, 0, 5, 1, 8, 3, 0, 4], dtype=np.int32)
+    inp = _as_bf16(synth.accept_inputs(300 + vocab, gamma, vocab, sigma))
+    got = _run_gpu(inp, offset_elems=offset, bf16=True)
+    bands = _check(inp, got)
+    assert bands["n_band_m"] + bands["n_band_tok"] <= 1
+
+
+def test_bf16_inputs_degenerate_rows():
+    """q = 0 at the draft token, a one-hot q that is rejected, all gamma zero: the special cases of the rule."""
+    V = 4096
+    inp = _as_bf16(synth.accept_inputs(13, np.array([1, 1, 0], dtype=np.int32), V, 1.0))
+    inp.q_probs[0, int(inp.draft_tokens[0])] = 0.0
+    inp.u_accept[0] = 0.999
+    t1 = int(inp.draft_tokens[1])
+    inp.q_probs[1] = 0.0
+    inp.q_probs[1, t1] = 1.0
+    inp.u_accept[1] = 0.99
+    got = _run_gpu(inp, bf16=True)
+    _check(inp, got)
+    assert got["accepted_len"][0] == 1 and np.isinf(got["ratio"][0])
+    assert got["accepted_len"][1] == 0 and got["next_token"][1] != t1
+
+
+@pytest.mark.parametrize("sigma", [0.3, 1.0, 3.0])
+def test_bf16_inputs_config2_full_size(sigma):
+    gamma = np.full(64, 8, dtype=np.int32)
+    inp = _as_bf16(synth.accept_inputs(synth.MASTER_SEED, gamma, 151936, sigma))
+    got = _run_gpu(inp, bf16=True)
+    bands = _check(inp, got)
+    print(f"bf16 inputs, sigma={sigma}: mean accepted/gamma = {got['accepted_len'].mean() / 8:.3f}, bands = {bands}")
     assert bands["n_band_m"] + bands["n_band_tok"] <= 2

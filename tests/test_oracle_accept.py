@@ -297,3 +297,27 @@ def test_resample_band_is_no_wider_than_the_rounding_it_excuses():
     tl0 = np.log(np.array([0.5, 1e-300, 0.5]))
     tl0[1] = -np.inf
     assert ar.resample_band(tl0, None, 0.5, 1e-5) == (0, 2) and ar.softmax(tl0)[1] == 0.0
+
+
+def test_output_law_when_the_verifier_sees_q_rounded_to_bfloat16():
+    """Reading behind gs_accept_reject_bf16: the draft token is sampled from q, the verifier applies the rule
+    with q~ = bfloat16(q).  The rule stays well defined (q~ need not sum to one) and the law of the emitted
+    token, enumerated exactly with the oracle's own ratio and residual routines, stays within 2^-8 of p in
+    total variation (q~/q is within 1 +- 2^-9); with the unrounded q it is p itself."""
+    from oracle.forward import round_bf16
+    rng = np.random.default_rng(61)
+    worst = 0.0
+    for _ in range(300):
+        V = int(rng.integers(3, 9))
+        p, q = _rand_dist(rng, V), _rand_dist(rng, V)
+        for q_seen, exact in ((q, True), (round_bf16(q), False)):
+            accept = np.array([min(1.0, ar.acceptance_ratio(p[s], q_seen[s])) for s in range(V)])
+            w = ar.residual_weights(p, q_seen)
+            law = q * accept + (1.0 - (q * accept).sum()) * w / w.sum()
+            tv = 0.5 * np.abs(law - p).sum()
+            if exact:
+                assert tv < 1e-12
+            else:
+                worst = max(worst, tv)
+                assert tv < 2.0 ** -8
+    assert worst > 1e-5          # the rounding does change the law: the bound is not vacuous

@@ -140,6 +140,15 @@ def test_small_f32_model_with_gqa_and_page_32():
     print("worst", r["worst"])
 
 
+@pytest.mark.parametrize("gamma", [[3, 1, 5], [16, 12, 9, 15, 11, 14]])
+def test_bf16_wide_vocabulary_statistics_from_the_lm_head_epilogue(gamma):
+    # V / 128 >= 192: the LM head takes the 8-wave kernel (12 rows) or the tall one (83 rows) as one launch, whose
+    # epilogue leaves the softmax statistics per column block; the accept stage merges them instead of
+    # reading the logits again.  The decisions below are therefore checked against the oracle on that path.
+    ms = synth.ModelShape(1, 128, 2, 1, 64, 256, 24576, 10000.0, dtype="bf16")
+    _run_case(ms, 86, np.array(gamma, np.int32), np.array([30, 0, 77, 5, 100, 64][:len(gamma)], np.int32), 16, std=0.08)
+
+
 def test_bf16_page_size_64_and_single_server():
     ms = synth.ModelShape(1, 256, 4, 1, 128, 512, 1024, 500000.0, dtype="bf16")
     _run_case(ms, 79, np.array([8], np.int32), np.array([700], np.int32), 64, std=0.08)
