@@ -161,6 +161,30 @@ def accept_leg(seed, bf16=False):
             "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "rejecting_servers": n_rej}
 
 
+def plain_read_leg():
+    """The practical ceiling of a read stream on this machine: gs_probe_stream_read over four rotated 1 GiB
+    buffers (together far beyond every cache), 40 timed launches."""
+    import torch
+    from paper_2512_09963_amd import binding as gsb
+    dev = torch.device("cuda:0")
+    bufs = [torch.full((1 << 30,), k + 1, dtype=torch.uint8, device=dev) for k in range(4)]
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device=dev)
+    for k in range(8):
+        gsb.gs_probe_stream_read(bufs[k % 4], sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 40
+    e0.record()
+    for k in range(iters):
+        gsb.gs_probe_stream_read(bufs[k % 4], sink)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / iters
+    gbs = (1 << 30) / us / 1e3
+    return {"kernel": "stream_read_kernel (1 GiB per launch, 16-byte non-temporal loads)", "us_per_launch": round(us, 2),
+            "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
 def cpu_baseline(ms, w, seed):
     """The oracle as it stands on the host cores, timed in full on the same workload: embedding, every decoder
     layer, final norm + LM head, softmax + accept/reject + resample.  Weights and cache contents are generated
@@ -302,6 +326,7 @@ def main():
     if not args.skip_accept_leg and args.workload == "cfg3":
         res["accept_kernel"] = accept_leg(seed)
         res["accept_kernel_bf16_inputs"] = accept_leg(seed, bf16=True)
+        res["plain_read_ceiling"] = plain_read_leg()
     if not args.skip_cpu_baseline and args.workload == "cfg3":
         res["cpu_baseline"] = cpu_baseline(ms, w, seed)
     print(json.dumps(res), flush=True)

@@ -308,6 +308,12 @@ gs_status gs_trace_residual(gs_ctx* ctx, float* trace);
 /* the summed milliseconds and the number of bracketed launches since the last  */
 /* read (arrays of GS_N_STAGES, host), and clears the record.                   */
 /* ------------------------------------------------------------------------- */
+/* Plain streaming read of `bytes` bytes at src (dev, 16-byte aligned): 16-byte non-temporal loads, four per lane
+ * in flight, nothing else.  Timing it gives the practical ceiling of a read stream on the machine at hand,
+ * against which bench.py states what the bandwidth-bound kernels reach.  sink: dev, at least 64 KiB (16384
+ * words, practically never written). */
+gs_status gs_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+
 enum { GS_STAGE_GEMM = 0, GS_STAGE_ATTENTION = 1, GS_STAGE_GLUE = 2, GS_STAGE_ACCEPT = 3, GS_N_STAGES = 4 };
 gs_status gs_profile_enable(gs_ctx* ctx, int on);
 gs_status gs_profile_read(gs_ctx* ctx, double* stage_ms, long* stage_launches);

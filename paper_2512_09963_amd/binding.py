@@ -24,7 +24,7 @@ _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4:
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_accept_reject_bf16", "gs_accept_reject_static",
            "gs_schedule_gamma", "gs_allocate_fixed", "gs_allocate_random",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_probe_stream_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -114,6 +114,8 @@ def lib():
             L.gs_pack_weight_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
             L.gs_trace_residual.restype = C.c_int
             L.gs_trace_residual.argtypes = [C.c_void_p, C.c_void_p]
+            L.gs_probe_stream_read.restype = C.c_int
+            L.gs_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
             L.gs_profile_read.restype = C.c_int
             L.gs_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -223,6 +225,11 @@ def gs_allocate_random(n, capacity, uniforms):
     nxt = np.zeros(int(n), dtype=np.int32)
     _check(lib().gs_allocate_random(int(n), int(capacity), u.ctypes.data, nxt.ctypes.data))
     return nxt
+
+
+def gs_probe_stream_read(src, sink, stream=None):
+    """Enqueues the plain streaming-read probe over the device tensor `src` (sink: >= 64 KiB device tensor)."""
+    _check(lib().gs_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
 
 
 def gs_pack_weight_w4(codes, scales, zeros, stream=None):

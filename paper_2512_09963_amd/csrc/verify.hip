@@ -160,6 +160,27 @@ __global__ void gather_draft_tokens_kernel(const int* __restrict__ tokens, const
   for (int j = threadIdx.x; j < gamma; j += blockDim.x) draft_tokens[r0 - srv + j] = tokens[r0 + 1 + j];
 }
 
+// Measurement aid (gs_probe_stream_read): the plainest possible streaming read, 16-byte non-temporal loads,
+// four per lane in flight, each workgroup folding its 16 KB pieces into one word.  What this kernel reaches is
+// the practical ceiling of a read stream on the machine at hand.
+typedef unsigned int probe_uint4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const probe_uint4* __restrict__ src, size_t n16,
+                                                          unsigned* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * 1024;
+  unsigned acc = 0;
+  for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
+    probe_uint4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const size_t j = i + (size_t)k * 256;
+      v[k] = j < n16 ? __builtin_nontemporal_load(src + j) : probe_uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+  }
+  if (acc == 0x9e3779b9u) sink[blockIdx.x] = acc;      // (keeps the loads alive; practically never stores)
+}
+
 // Debug check of the device-resident descriptor (gs_check_batch).  One workgroup per server; the first
 // inconsistency found is recorded as (kind, server, index, value) with a compare-and-swap on err[0].
 enum { kBadCuRows = 1, kBadCtxLen = 2, kBadToken = 3, kBadPage = 4 };
@@ -516,4 +537,15 @@ extern "C" gs_status gs_check_batch(const gs_ctx* ctx, const gs_kv_cache* kv, co
     case kBadToken: return gs::fail(GS_EINVAL, "tokens[%d] = %d of server %d is outside the vocabulary", err[2], err[3], err[1]);
     default: return gs::fail(GS_EINVAL, "block_table[%d][%d] = %d is not a page of the cache", err[1], err[2], err[3]);
   }
+}
+
+extern "C" gs_status gs_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || bytes < 16) return gs::fail(GS_EINVAL, "null argument or fewer than 16 bytes");
+  if (reinterpret_cast<uintptr_t>(src) % 16) return gs::fail(GS_EINVAL, "source must be 16-byte aligned");
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>((n16 + 1023) / 1024, 16384);
+  stream_read_kernel<<<grid, 256, 0, static_cast<hipStream_t>(hip_stream)>>>(
+      static_cast<const probe_uint4*>(src), n16, static_cast<unsigned*>(sink));
+  GS_LAUNCH_CHECK("stream_read");
+  return GS_OK;
 }

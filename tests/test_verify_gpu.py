@@ -307,3 +307,17 @@ def test_check_batch_names_the_first_violation_and_bad_token_ids_are_never_used_
     with pytest.raises(gsb.GsError) as e:
         check(bad)
     assert "block_table[1][0]" in str(e.value)
+
+
+def test_stream_read_probe_runs_and_validates_its_arguments():
+    """Measurement aid of bench.py: enqueues, leaves the source untouched, rejects a misaligned source."""
+    import torch
+    from paper_2512_09963_amd import binding as gsb
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda:0")
+    gsb.gs_probe_stream_read(src, sink)
+    gsb.gs_probe_stream_read(src[:1001], sink)              # ragged size
+    torch.cuda.synchronize()
+    assert int(src[-1]) == (1 << 20) - 1
+    with pytest.raises(gsb.GsError):
+        gsb.gs_probe_stream_read(src[1:], sink)
