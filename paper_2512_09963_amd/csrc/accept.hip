@@ -154,21 +154,34 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(const T* __res
 }
 
 // merge_stats: the statistics of a row from the per-column-block pairs that the LM-head projection left
-// (stats [rows][n_blocks]).  grid rows, one wavefront: lanes stride over the blocks, then a fixed-order merge.
-__global__ __launch_bounds__(64) void merge_stats_kernel(const float2* __restrict__ stats, int n_blocks,
-                                                         float2* __restrict__ row_stat) {
-  const int row = blockIdx.x, lane = threadIdx.x;
+// (stats [rows][n_blocks]).  grid rows, 256 lanes: every lane issues its (up to four at a time) loads back to
+// back, then a fixed-order merge over the lanes of a wave and over the waves.
+__global__ __launch_bounds__(256) void merge_stats_kernel(const float2* __restrict__ stats, int n_blocks,
+                                                          float2* __restrict__ row_stat) {
+  const int row = blockIdx.x, tid = threadIdx.x;
   const float2* p = stats + (size_t)row * n_blocks;
   float m = -INFINITY, s = 0.f;
-  for (int b = lane; b < n_blocks; b += 64) {
-    const float2 v = p[b];
-    merge_pair(m, s, v.x, v.y);
+  for (int b0 = tid; b0 < n_blocks; b0 += 4 * 256) {
+    float2 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = (b0 + k * 256 < n_blocks) ? p[b0 + k * 256] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) merge_pair(m, s, v[k].x, v[k].y);
   }
   for (int off = 32; off > 0; off >>= 1) {
     const float m2 = __shfl_down(m, off), s2 = __shfl_down(s, off);
     merge_pair(m, s, m2, s2);
   }
-  if (lane == 0) row_stat[row] = make_float2(m, s);
+  __shared__ float sm[4], ss[4];
+  if ((tid & 63) == 0) {
+    sm[tid >> 6] = m;
+    ss[tid >> 6] = s;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w) merge_pair(m, s, sm[w], ss[w]);
+    row_stat[row] = make_float2(m, s);
+  }
 }
 
 // Weight of token t in the draw: max(0, p - q) or p.
@@ -554,7 +567,7 @@ gs_status launch_accept_t(const AcceptPlan& p, int n_servers, int n_rows, const 
                           const void* row_stats, int n_stat_blocks) {
   int n_chunks = p.n_chunks;
   if (row_stats) {      // one pair per row, merged from the producer's column-block pairs
-    merge_stats_kernel<<<n_rows, 64, 0, stream>>>(static_cast<const float2*>(row_stats), n_stat_blocks, p.partial);
+    merge_stats_kernel<<<n_rows, 256, 0, stream>>>(static_cast<const float2*>(row_stats), n_stat_blocks, p.partial);
     GS_LAUNCH_CHECK("merge_stats");
     n_chunks = 1;
   } else {

@@ -50,6 +50,26 @@ __device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s
   m = M;
 }
 
+// Reductions over the 16 lanes of a DPP row (lanes 16 g .. 16 g + 15) with data-parallel-primitive moves, which
+// are modifiers of ordinary vector instructions (a shuffle through the LDS crossbar costs an LDS instruction
+// each): neighbours in a quad, the other pair of the quad, the mirrored quad of the half row, the mirrored half.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));      // quad_perm(1, 0, 3, 2)
+  v = fmaxf(v, dpp_move<0x4E>(v));      // quad_perm(2, 3, 0, 1)
+  v = fmaxf(v, dpp_move<0x141>(v));     // row_half_mirror
+  return fmaxf(v, dpp_move<0x140>(v));  // row_mirror
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  return v + dpp_move<0x140>(v);
+}
+
 // STATS (LM head, one K split): the epilogue also reduces every output row over the workgroup's columns to the
 // pair (max, sum exp(y - max)) and stores it at stats[row][column block], so that the vocabulary softmax
 // statistics (Section II-A-1) come out of the projection and the logits need not be read again for them.
@@ -178,12 +198,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16_t*
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float v = acc[mt][i];
-        float mx = v;
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-        float e = __expf(v - mx);
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) e += __shfl_xor(e, off);
+        const float mx = row16_max(v);
+        const float e = row16_sum(__expf(v - mx));
         if (c == 0) st[wave][mt * 16 + g * 4 + i] = make_float2(mx, e);
       }
     __syncthreads();
@@ -446,13 +462,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tall_kernel(const bf16_t* __
         float mx = acc[mt][0][i];
 #pragma unroll
         for (int nt = 1; nt < NT; ++nt) mx = fmaxf(mx, acc[mt][nt][i]);
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        mx = row16_max(mx);
         float e = 0.f;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) e += __expf(acc[mt][nt][i] - mx);
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) e += __shfl_xor(e, off);
+        e = row16_sum(e);
         if (c == 0) st[wave][mt * 16 + g * 4 + i] = make_float2(mx, e);
       }
     __syncthreads();
