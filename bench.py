@@ -210,6 +210,8 @@ def cpu_baseline(ms, w, seed):
         x = fw.layer_forward(ms, x, W, k, v, batch.gamma, batch.ctx_len, batch.block_table, batch.page_size)
         t_fwd += time.perf_counter() - t0
         del W, k, v
+        if (l + 1) % 8 == 0:
+            print(f"[bench] cpu baseline: oracle layer {l + 1}/{ms.n_layers}", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
     logits = fw.lm_head(ms, x, top)
     t_fwd += time.perf_counter() - t0

@@ -27,14 +27,19 @@ def to_device(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a)).to(_dev()).to(dtype)
 
 
-def _progress(msg):
+def _progress(msg, sink=True):
+    """Progress line of a long upload: to `sink` if it is callable, else to stderr."""
+    if callable(sink):
+        sink(msg)
+        return
     import sys
     print(msg, file=sys.stderr, flush=True)
 
 
 def upload_model(ms: synth.ModelShape, top: dict, get_layer, progress=False):
     """Returns a binding.Verifier for weights given as float32 numpy arrays (for ms.dtype "w4" the projection
-    matrices are given as (codes, scales, zeros) triples instead)."""
+    matrices are given as (codes, scales, zeros) triples instead).  progress: False, True (lines to stderr) or a
+    callable that takes the line."""
     dt = storage_dtype(ms)
     if ms.dtype == "w4":
         # a projection matrix arrives as a 4-bit checkpoint triple (codes, scales, zeros), see synth.quantize_w4
@@ -52,7 +57,7 @@ def upload_model(ms: synth.ModelShape, top: dict, get_layer, progress=False):
         layers.append({k: packed(W[k]) for k in ("wqkv", "wo", "wgu", "wd")} |
                       {k: to_device(W[k], torch.float32) for k in ("norm1", "norm2")})
         if progress and (l + 1) % 8 == 0:
-            _progress(f"[workload] uploaded {l + 1}/{ms.n_layers} layers")
+            _progress(f"[workload] uploaded {l + 1}/{ms.n_layers} layers", progress)
     desc = dict(n_layers=ms.n_layers, d_model=ms.d_model, n_heads=ms.n_heads, n_kv_heads=ms.n_kv_heads,
                 head_dim=ms.head_dim, d_ffn=ms.d_ffn, vocab=ms.vocab, rope_theta=ms.rope_theta, rms_eps=ms.rms_eps,
                 dtype=ms.dtype)
@@ -151,6 +156,6 @@ def upload_config(cfg: synth.VerifyConfig, ver=None, progress=False):
         kv.set_layer(l, synth.kv_layer_cache(gen, seed, l, "k", batch.n_pages, batch.page_size),
                      synth.kv_layer_cache(gen, seed, l, "v", batch.n_pages, batch.page_size))
         if progress and (l + 1) % 16 == 0:
-            _progress(f"[workload] KV of {l + 1}/{ms.n_layers} layers in place")
+            _progress(f"[workload] KV of {l + 1}/{ms.n_layers} layers in place", progress)
     db = DeviceBatch(batch, cfg.tokens, cfg.q_probs, cfg.u_accept, cfg.u_resample)
     return ver, kv, db

@@ -24,6 +24,7 @@ from oracle import forward as fw
 from oracle import schedule as sch
 from paper_2512_09963_amd import synth
 from tests import f32_forward as f32
+from tests.conftest import progress
 from tests.parity import check_accept_outputs
 from tests.test_verify_gpu import assert_logits_close
 
@@ -140,8 +141,8 @@ def _verify_and_compare(cfg, ver, kv, db, state=None, with_f32=True):
             _record_rows(l, b, k_32, v_32, state.f32)
             del k_32, v_32
         del W, k_tf, v_tf, k_fr, v_fr
-        if (l + 1) % 8 == 0:
-            print(f"[oracle] {cfg.name}: layer {l + 1}/{ms.n_layers} checked", flush=True)
+        if (l + 1) % 4 == 0:
+            progress(f"{cfg.name}: layer {l + 1}/{ms.n_layers} checked against the oracle")
     assert worst_layer <= 2e-2, f"teacher-forced layer output error / row scale = {worst_layer:.3g}"
     assert worst_kv <= 2e-2, f"appended K/V rows: {worst_kv:.3g}"
     head_err = assert_logits_close(got_logits, fw.lm_head(ms, tr[ms.n_layers], top), 2e-2, "teacher-forced logits")
@@ -183,7 +184,7 @@ def _verify_and_compare(cfg, ver, kv, db, state=None, with_f32=True):
         width = probability_band(want_free[rows_of_draft[j]][None, :], bound)[0] * r_o
         assert abs(float(cfg.u_accept[j]) - r_o) <= width + 1e-5, \
             f"server {i}: accepted {m_g}, oracle with its own logits {m_o}; u = {cfg.u_accept[j]:.6f}, ratio = {r_o:.6f}"
-    print(f"{cfg.name}: layers {ms.n_layers}, rows {b.n_rows}: teacher-forced layer err {worst_layer:.2e}, K/V rows "
+    progress(f"{cfg.name}: layers {ms.n_layers}, rows {b.n_rows}: teacher-forced layer err {worst_layer:.2e}, K/V rows "
           f"{worst_kv:.2e}, head {head_err:.2e}, |dp|/p {p_tf:.2e}; free-running logits err/scale {free_err:.2e} "
           f"(bound {bound:.2e}; float32 CPU forward {cpu_err if cpu_err is None else round(cpu_err, 5)}), |dp|/p {p_free:.2e}; "
           f"bands {bands}; accepted {got['accepted_len'].tolist()}; "
@@ -194,7 +195,7 @@ def _verify_and_compare(cfg, ver, kv, db, state=None, with_f32=True):
 def test_config3_llama8b_shape_full_size():
     from paper_2512_09963_amd import workload as wl
     cfg = synth.config3()
-    ver, kv, db = wl.upload_config(cfg, progress=True)
+    ver, kv, db = wl.upload_config(cfg, progress=progress)
     _verify_and_compare(cfg, ver, kv, db)
 
 
@@ -202,7 +203,7 @@ def test_config4_ragged_paged_full_depth():
     """32 servers, ragged gamma and context, permuted pages, all 32 layers: one verification step."""
     from paper_2512_09963_amd import workload as wl
     cfg = synth.config4()
-    ver, kv, db = wl.upload_config(cfg, progress=True)
+    ver, kv, db = wl.upload_config(cfg, progress=progress)
     _verify_and_compare(cfg, ver, kv, db, with_f32=FULL)       # (measured once with it: device 2.64e-2, CPU 2.37e-2)
 
 
@@ -212,7 +213,7 @@ def test_config4_ragged_paged_with_scheduler_in_the_loop():
     from paper_2512_09963_amd import binding as gsb, workload as wl
     ms = synth.LLAMA3_8B if FULL else dataclasses.replace(synth.LLAMA3_8B, n_layers=4)
     cfg = synth.config4(ms=ms)
-    ver, kv, db = wl.upload_config(cfg, progress=True)
+    ver, kv, db = wl.upload_config(cfg, progress=progress)
     n, C = cfg.batch.n_servers, 272
     alpha, X = np.full(n, 0.5), np.ones(n)
     alpha_o, X_o = alpha.copy(), X.copy()
@@ -245,6 +246,6 @@ def test_config5_llama70b_shape():
     from paper_2512_09963_amd import workload as wl
     ms = synth.LLAMA3_70B if FULL else dataclasses.replace(synth.LLAMA3_70B, n_layers=36)
     cfg = synth.config5(ms=ms)
-    ver, kv, db = wl.upload_config(cfg, progress=True)
+    ver, kv, db = wl.upload_config(cfg, progress=progress)
     assert kv.k[ms.n_layers - 1].data_ptr() - kv.k.data_ptr() > 1 << 32
     _verify_and_compare(cfg, ver, kv, db, with_f32=FULL)       # (the float32 CPU forward costs a minute here)
