@@ -24,10 +24,10 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 
 # HBM bytes per projection launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-# profiles/hbm_traffic_counters.md (121.82 MB fetched + 7.82 MB written, scaled by the copy-kernel factors
+# profiles/hbm_traffic_counters.md (121.79 MB fetched + 5.34 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
-GEMM_TRAFFIC = {"gemm_hip_sha256": "e95585e275602f49bb6b8a7cce30ebe7f6daff6f5b4fc6721624f02eb0a1f807",
-                "bytes_per_launch": 127129895}
+GEMM_TRAFFIC = {"gemm_hip_sha256": "def0d05baaf8661cf2cf8a42697f8573210332859236e6e404e9fda1c04617e1",
+                "bytes_per_launch": 127131062}
 
 
 def measured_traffic():
