@@ -95,7 +95,8 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA path.  grid (work list entries, H_kv), NW waves per workgroup.
 //
-// A workgroup owns steps [split * steps_per_split, ...) of one (server, KV head); a step is 32
+// A workgroup owns one split of one (server, KV head): a server's steps are dealt evenly to its
+// ceil(steps / steps_per_split) splits; a step is 32
 // keys = two 16-key tiles = 16 KB of K and V at hd 128.  K/V go from global memory straight into
 // a two-stage LDS buffer with direct global->LDS loads (no register staging).  A stage has four
 // parts, K and V of either tile; part p is loaded by wave p % NW (waves 0..3 when NW > 4), whose
@@ -163,7 +164,9 @@ __global__ __launch_bounds__(256) void attn_work_kernel(const int* __restrict__ 
     for (int s = 0; s < count && first + s < capacity; ++s) {
       AttnWork w;
       w.srv = srv; w.split = s; w.row0 = row0; w.n_tokens = T; w.ctx = L; w.pad = 0;
-      const int key0 = min(s * steps_per_split * 32, last_tile_key), key1 = min(key0 + 16, last_tile_key);
+      // (the server's steps are dealt evenly to its splits, as in attn_kernel)
+      const int steps = (L + T + 31) >> 5, base = steps / count, rem = steps - base * count;
+      const int key0 = min((s * base + min(s, rem)) * 32, last_tile_key), key1 = min(key0 + 16, last_tile_key);
       w.page0 = block_table[(size_t)srv * max_blocks + key0 / page_size];
       w.page1 = block_table[(size_t)srv * max_blocks + key1 / page_size];
       entries[first + s] = w;
@@ -230,9 +233,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1
   const int g = lane >> 4, c = lane & 15;            // loader roles
   const int n_keys = L + T;
   const int n_steps_all = (n_keys + 31) >> 5;
-  const int step_begin = split * steps_per_split;
-  if (step_begin >= n_steps_all) return;
-  const int n = min(steps_per_split, n_steps_all - step_begin);
+  // the server's steps are dealt evenly to its ceil(steps / steps_per_split) splits (sizes differ by at most
+  // one): a short remainder split would leave its slot idle while the full-length ones decide the duration
+  const int n_splits = (n_steps_all + steps_per_split - 1) / steps_per_split;
+  if (split >= n_splits) return;
+  const int base_steps = n_steps_all / n_splits, extra = n_steps_all - base_steps * n_splits;
+  const int step_begin = split * base_steps + min(split, extra);
+  const int n = base_steps + (split < extra ? 1 : 0);
   const int* bt = block_table + (size_t)srv * max_blocks;
   const bool page_pow2 = (page_size & (page_size - 1)) == 0;
   const int page_shift = 31 - __builtin_clz(page_size);
@@ -507,20 +514,65 @@ __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const f
 // (splits <= total / steps + one ragged tail per server and KV head), which also keeps the partial results
 // few (measured on the 70B shape: 5.9 instead of 6.7 ms per step against two rounds); a floor on the steps
 // per workgroup bounds what the partial results cost on small batches.
-void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, long total_steps, int max_steps,
-                    int* steps_per_split, int* max_splits) {
+void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, const int* gamma_host,
+                    const int* ctx_len_host, int* steps_per_split, int* max_splits) {
   const int tiles = ceil_div(max_block_tokens * group, 32);
   const int waves = tiles < 8 ? (tiles > 0 ? tiles : 1) : 8;
   constexpr int kWavesPerCu = 12;    // by registers (three waves per SIMD)
   const int wgs_per_cu = kWavesPerCu / waves < 5 ? (kWavesPerCu / waves > 0 ? kWavesPerCu / waves : 1) : 5;   // 5 workgroups by LDS
-  const long slots = 256L * wgs_per_cu;
-  long room = slots - (long)n_servers * n_kv;      // slots left for the full-length splits
-  if (room < slots / 2) room = slots / 2;
-  long sps = (total_steps * n_kv + room - 1) / room;
-  if (sps < 6) sps = 6;
-  const long lo = (max_steps + 31) / 32;                        // at most 32 splits per server
-  if (sps < lo) sps = lo;
-  if (sps > max_steps) sps = max_steps > 0 ? max_steps : 1;
+  constexpr long kCus = 256;
+  const long slots = kCus * wgs_per_cu;
+  auto steps_of = [&](int i) { return (long)(ctx_len_host[i] + gamma_host[i] + 1 + 31) / 32; };
+  long total_steps = 0, max_steps = 1;
+  for (int i = 0; i < n_servers; ++i) {
+    total_steps += steps_of(i);
+    if (steps_of(i) > max_steps) max_steps = steps_of(i);
+  }
+  // workgroups of a launch with splits of at most t steps, and the longest split among them
+  auto workgroups = [&](long t, long* longest) {
+    long c = 0, top = 0;
+    for (int i = 0; i < n_servers; ++i) {
+      const long n = (steps_of(i) + t - 1) / t;
+      c += n;
+      if (n > 0 && (steps_of(i) + n - 1) / n > top) top = (steps_of(i) + n - 1) / n;
+    }
+    if (longest) *longest = top;
+    return c * n_kv;
+  };
+  long lo = (max_steps + 31) / 32;                        // at most 32 splits per server
+  if (lo < 6) lo = 6;                                     // at least 6 steps per split (partial-result traffic)
+  if (lo > max_steps) lo = max_steps;
+  const long fit = slots - slots / 16;                    // all resident at once, with some slack for placement
+  long sps;
+  if (workgroups(max_steps, nullptr) <= fit) {
+    // the shortest splits whose workgroups are all resident at once ...
+    long a = lo, b = max_steps;
+    while (a < b) {
+      const long mid = (a + b) / 2;
+      if (workgroups(mid, nullptr) <= fit) b = mid; else a = mid + 1;
+    }
+    sps = a;
+    // ... unless somewhat longer ones load the busiest compute unit less: (workgroups per CU, rounded up) x
+    // (steps of the longest split), e.g. 3 x 22 instead of 4 x 19 steps at the 70B shape with 16 servers
+    auto cu_load = [&](long t) {
+      long longest = 0;
+      const long w = workgroups(t, &longest);
+      return (w + kCus - 1) / kCus * longest;
+    };
+    long best = cu_load(sps);
+    for (long t = sps + 1; t <= sps + sps / 4 && t <= max_steps; ++t) {
+      const long l = cu_load(t);
+      if (l < best) {
+        best = l;
+        sps = t;
+      }
+    }
+  } else {
+    // more (server, KV head) pairs than slots: several rounds of workgroups anyway
+    sps = (total_steps * n_kv + slots / 2 - 1) / (slots / 2);
+    if (sps < lo) sps = lo;
+    if (sps > max_steps) sps = max_steps;
+  }
   *steps_per_split = (int)sps;
   // the split count is also the stride (in 512-byte partial rows) between the partial results of
   // neighbouring (row, head) pairs: kept odd, because a power-of-two stride sends all partial stores of a

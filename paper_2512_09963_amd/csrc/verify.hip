@@ -29,8 +29,8 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
                              const void* rope, int page_size, int n_heads, int n_kv, int hd, void* q_out,
                              void* k_pages, void* v_pages, hipStream_t stream);
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
-void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, long total_steps, int max_steps,
-                    int* steps_per_split, int* max_splits);
+void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, const int* gamma_host,
+                    const int* ctx_len_host, int* steps_per_split, int* max_splits);
 size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits);
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
@@ -384,7 +384,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   const int act = m.dtype == GS_W4 ? GS_BF16 : m.dtype;     // storage type of activations, KV pages, embedding
   if (act == GS_BF16 && kv->page_size % 16 != 0)
     return gs::fail(GS_ESHAPE, "bf16 attention needs a page size that is a multiple of 16");
-  long R = 0, G = 0, total_steps = 0;
+  long R = 0, G = 0;
   int max_t = 0, max_ctx = 0;
   for (int i = 0; i < n; ++i) {
     const int g = b->gamma_host[i], L = b->ctx_len_host[i];
@@ -397,7 +397,6 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
     G += g;
     max_t = std::max(max_t, g + 1);
     max_ctx = std::max(max_ctx, L + g + 1);
-    total_steps += (L + g + 1 + 31) / 32;
   }
   if (R > (1 << 20)) return gs::fail(GS_EINVAL, "too many rows");
   const bool do_accept = b->q_probs != nullptr;
@@ -414,7 +413,7 @@ extern "C" gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const g
   const int F = m.d_ffn;
   const size_t layer_stride = (size_t)kv->n_pages * m.n_kv_heads * kv->page_size * m.head_dim * ctx->elem;
   int attn_sps = 1, attn_splits = 1;
-  gs::attention_plan(m.n_kv_heads, m.n_heads / m.n_kv_heads, max_t, n, total_steps, (max_ctx + 31) / 32, &attn_sps,
+  gs::attention_plan(m.n_kv_heads, m.n_heads / m.n_kv_heads, max_t, n, b->gamma_host, b->ctx_len_host, &attn_sps,
                      &attn_splits);
   gs_status st;
 #define GS_TRY(call)          \
