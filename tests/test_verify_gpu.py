@@ -209,6 +209,17 @@ def test_bf16_more_servers_than_one_round_of_the_attention_work_list():
     _run_case(ms, 85, gamma, ctx, 16, std=0.08)
 
 
+def test_bf16_more_server_head_pairs_than_resident_workgroups():
+    # 200 servers x 8 KV heads = 1600 (server, head) pairs, more than the attention launch keeps resident at once:
+    # the planner's several-rounds branch, with a few contexts long enough for many uneven splits
+    ms = synth.ModelShape(1, 128, 8, 8, 64, 128, 512, 10000.0, dtype="bf16")
+    rng = np.random.default_rng(86)
+    gamma = rng.integers(0, 3, 200).astype(np.int32)
+    ctx = rng.integers(0, 60, 200).astype(np.int32)
+    ctx[[0, 77, 199]] = [1300, 2500, 845]
+    _run_case(ms, 86, gamma, ctx, 16, std=0.08)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_bf16_seeded_random_shapes(seed):
     # model widths, head layout, page size, server count, draft lengths and contexts drawn from the seed: walks the
