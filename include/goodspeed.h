@@ -296,6 +296,16 @@ gs_status gs_verify_batch(gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* ba
 gs_status gs_check_batch(const gs_ctx* ctx, const gs_kv_cache* kv, const gs_batch* batch, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* Host-only aid (no GPU call): the launch plan of the ragged attention (Section II-A-1's target forward over
+ * N contexts of different length) that gs_verify_batch would use for a batch of this geometry.  n_kv_heads,
+ * group = query heads per KV head; gamma_host, ctx_len_host: host, [n_servers].  Out: steps_per_split = the
+ * longest run of 32-key steps one workgroup takes (a server with s steps is cut into ceil(s / steps_per_split)
+ * splits of equal length up to one step); n_workgroups = (server, split, KV head) items of the launch;
+ * busiest_cu_steps = the most steps any of the 256 compute units is dealt.  GS_EINVAL on negative entries. */
+gs_status gs_plan_attention(int n_kv_heads, int group, int n_servers, const int* gamma_host,
+                            const int* ctx_len_host, int* steps_per_split, long* n_workgroups,
+                            long* busiest_cu_steps);
+
 /* Test aid: with a non-NULL `trace` (dev, fp32 [(n_layers + 1)][R][d_model], caller-owned),
  * every later gs_verify_batch on this ctx also copies the residual stream entering each decoder
  * layer, and the final one that feeds the last norm, into it.  NULL switches it off. */

@@ -24,7 +24,7 @@ _STATUS = {0: "GS_OK", -1: "GS_EINVAL", -2: "GS_ESHAPE", -3: "GS_ECAPACITY", -4:
 
 EXPORTS = ["gs_last_error", "gs_accept_workspace_bytes", "gs_accept_reject", "gs_accept_reject_bf16", "gs_accept_reject_static",
            "gs_schedule_gamma", "gs_allocate_fixed", "gs_allocate_random",
-           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_probe_stream_read", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
+           "gs_create", "gs_destroy", "gs_workspace_bytes", "gs_verify_batch", "gs_check_batch", "gs_profile_enable", "gs_profile_read", "gs_probe_stream_read", "gs_plan_attention", "gs_trace_residual", "gs_pack_weight", "gs_w4_packed_bytes", "gs_pack_weight_w4"]
 STAGES = ["gemm", "attention", "glue", "accept"]
 
 
@@ -116,6 +116,9 @@ def lib():
             L.gs_trace_residual.argtypes = [C.c_void_p, C.c_void_p]
             L.gs_probe_stream_read.restype = C.c_int
             L.gs_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+            L.gs_plan_attention.restype = C.c_int
+            L.gs_plan_attention.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
             L.gs_profile_read.restype = C.c_int
             L.gs_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -225,6 +228,18 @@ def gs_allocate_random(n, capacity, uniforms):
     nxt = np.zeros(int(n), dtype=np.int32)
     _check(lib().gs_allocate_random(int(n), int(capacity), u.ctypes.data, nxt.ctypes.data))
     return nxt
+
+
+def gs_plan_attention(n_kv_heads, group, gamma, ctx_len):
+    """Host-only: (steps_per_split, n_workgroups, busiest_cu_steps) of the attention launch for this geometry."""
+    g = np.ascontiguousarray(gamma, dtype=np.int32)
+    c = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    if g.shape != c.shape:
+        raise ValueError("gamma and ctx_len must have one entry per server")
+    sps, n, busy = C.c_int(0), C.c_long(0), C.c_long(0)
+    _check(lib().gs_plan_attention(int(n_kv_heads), int(group), int(g.size), g.ctypes.data, c.ctypes.data,
+                                   C.addressof(sps), C.addressof(n), C.addressof(busy)))
+    return sps.value, n.value, busy.value
 
 
 def gs_probe_stream_read(src, sink, stream=None):

@@ -18,7 +18,9 @@
 // fp32 path: one wave per (row, head), lanes over keys, online softmax per lane.
 #include "common.h"
 #include "device_types.h"
+#include <algorithm>
 #include <cmath>
+#include <limits>
 
 namespace gs {
 namespace {
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA path.  grid (work list entries, H_kv), NW waves per workgroup.
+// bf16 MFMA path.  1-D grid over the (work list entry, KV head) items (item_of_workgroup), NW waves per workgroup.
 //
 // A workgroup owns one split of one (server, KV head): a server's steps are dealt evenly to its
 // ceil(steps / steps_per_split) splits; a step is 32
@@ -128,30 +130,54 @@ struct AttnWork {
 };
 static_assert(sizeof(AttnWork) == 32, "entries are read as one 32-byte load");
 
-// One workgroup; a lane owns a server (in rounds of 256 servers), a scan over the servers' split counts
-// gives the position of its entries.  Entries beyond the capacity are dropped (cannot happen when the
-// host's copy of the batch geometry matches the device's).
+// One workgroup.  The entries are written in the order of decreasing split length (counting sort over the
+// lengths, which the splits of a server take only two of), because the hardware deals the workgroups of a
+// launch to the compute units round robin by their linear index and a compute unit's finishing time follows
+// the sum of the steps it was dealt: attn_kernel walks the sorted list in a serpentine (item_of_workgroup),
+// so every compute unit gets one long, one medium, ... split instead of whatever the server order brings.
+// Splits longer than kSortBins - 1 steps are not sorted (server order).  Entries beyond the capacity are
+// dropped (cannot happen when the host's copy of the batch geometry matches the device's).
+constexpr int kSortBins = 1024;
+
 __global__ __launch_bounds__(256) void attn_work_kernel(const int* __restrict__ cu_rows,
                                                         const int* __restrict__ ctx_len, int n_servers,
                                                         const int* __restrict__ block_table, int max_blocks,
                                                         int page_size, int steps_per_split, int capacity,
                                                         int* __restrict__ list) {
+  __shared__ int bin[kSortBins];      // entries per split length, then the first position of a length
   __shared__ int scan[256];
-  __shared__ int base_sh;
+  __shared__ int total_sh;
   const int tid = threadIdx.x;
-  if (tid == 0) base_sh = 0;
+  const bool sorted = steps_per_split < kSortBins;
+  for (int b = tid; b < kSortBins; b += 256) bin[b] = 0;
+  if (tid == 0) total_sh = 0;
   __syncthreads();
-  AttnWork* entries = reinterpret_cast<AttnWork*>(list + 8);
-  for (int c0 = 0; c0 < n_servers; c0 += 256) {
-    const int srv = c0 + tid;
-    int count = 0, row0 = 0, T = 0, L = 0;
-    if (srv < n_servers) {
-      row0 = cu_rows[srv];
-      T = cu_rows[srv + 1] - row0;
-      L = ctx_len[srv];
-      count = (((L + T + 31) >> 5) + steps_per_split - 1) / steps_per_split;
+  // a server's splits: count of them, `rem` of base + 1 steps followed by count - rem of base steps
+  auto shape = [&](int srv, int& row0, int& T, int& L, int& count, int& base, int& rem) {
+    row0 = cu_rows[srv];
+    T = cu_rows[srv + 1] - row0;
+    L = ctx_len[srv];
+    const int steps = (L + T + 31) >> 5;
+    count = (steps + steps_per_split - 1) / steps_per_split;
+    base = count > 0 ? steps / count : 0;
+    rem = steps - base * count;
+  };
+  if (sorted) {
+    for (int srv = tid; srv < n_servers; srv += 256) {
+      int row0, T, L, count, base, rem;
+      shape(srv, row0, T, L, count, base, rem);
+      if (rem > 0) atomicAdd(&bin[base + 1], rem);
+      if (count - rem > 0) atomicAdd(&bin[base], count - rem);
     }
-    scan[tid] = count;
+    __syncthreads();
+    // first position of each length, longest first: lane t owns bins kSortBins - 1 - 4 t down to ... - 3
+    int mine[4], sum = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      mine[k] = bin[kSortBins - 1 - (4 * tid + k)];
+      sum += mine[k];
+    }
+    scan[tid] = sum;
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {
       const int v = tid >= off ? scan[tid - off] : 0;
@@ -159,23 +185,71 @@ __global__ __launch_bounds__(256) void attn_work_kernel(const int* __restrict__ 
       scan[tid] += v;
       __syncthreads();
     }
-    const int first = base_sh + scan[tid] - count;
-    const int last_tile_key = ((L + T - 1) >> 4) << 4;
-    for (int s = 0; s < count && first + s < capacity; ++s) {
-      AttnWork w;
-      w.srv = srv; w.split = s; w.row0 = row0; w.n_tokens = T; w.ctx = L; w.pad = 0;
-      // (the server's steps are dealt evenly to its splits, as in attn_kernel)
-      const int steps = (L + T + 31) >> 5, base = steps / count, rem = steps - base * count;
-      const int key0 = min((s * base + min(s, rem)) * 32, last_tile_key), key1 = min(key0 + 16, last_tile_key);
-      w.page0 = block_table[(size_t)srv * max_blocks + key0 / page_size];
-      w.page1 = block_table[(size_t)srv * max_blocks + key1 / page_size];
-      entries[first + s] = w;
+    int at = scan[tid] - sum;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      bin[kSortBins - 1 - (4 * tid + k)] = at;
+      at += mine[k];
     }
-    __syncthreads();
-    if (tid == 255) base_sh += scan[255];
+    if (tid == 255) total_sh = scan[255];
     __syncthreads();
   }
-  if (tid == 0) list[0] = min(base_sh, capacity);
+  AttnWork* entries = reinterpret_cast<AttnWork*>(list + 8);
+  for (int c0 = 0; c0 < n_servers; c0 += 256) {
+    const int srv = c0 + tid;
+    int row0 = 0, T = 0, L = 0, count = 0, base = 0, rem = 0;
+    if (srv < n_servers) shape(srv, row0, T, L, count, base, rem);
+    int first_long = 0, first_short = 0;      // positions of the server's base + 1 and base step splits
+    if (sorted) {
+      if (rem > 0) first_long = atomicAdd(&bin[base + 1], rem);
+      if (count - rem > 0) first_short = atomicAdd(&bin[base], count - rem);
+    } else {
+      scan[tid] = count;
+      __syncthreads();
+      for (int off = 1; off < 256; off <<= 1) {
+        const int v = tid >= off ? scan[tid - off] : 0;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+      }
+      first_long = total_sh + scan[tid] - count;
+      first_short = first_long + rem;
+      __syncthreads();
+      if (tid == 255) total_sh += scan[255];
+      __syncthreads();
+    }
+    const int last_tile_key = ((L + T - 1) >> 4) << 4;
+    for (int sp = 0; sp < count; ++sp) {
+      const int pos = sp < rem ? first_long + sp : first_short + (sp - rem);
+      if (pos >= capacity) continue;
+      AttnWork w;
+      w.srv = srv; w.split = sp; w.row0 = row0; w.n_tokens = T; w.ctx = L; w.pad = 0;
+      // (the server's steps are dealt evenly to its splits, as in attn_kernel)
+      const int key0 = min((sp * base + min(sp, rem)) * 32, last_tile_key), key1 = min(key0 + 16, last_tile_key);
+      w.page0 = block_table[(size_t)srv * max_blocks + key0 / page_size];
+      w.page1 = block_table[(size_t)srv * max_blocks + key1 / page_size];
+      entries[pos] = w;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) list[0] = min(total_sh, capacity);
+}
+
+// Which (work list entry, KV head) a workgroup of the 1-D attention grid takes: the items, entry-major (the KV
+// heads of an entry are neighbours, so they go to the 8 XCDs), in rounds of one item per compute unit, the
+// rounds alternately forwards and backwards, counted from the last one, which is taken forwards (it may be
+// partial, and the grid has no workgroup beyond the items: padding workgroups in the middle of a launch that
+// fills every slot kept the last workgroups of one XCD waiting for a slot).  The list being sorted by
+// length, the sums of the items that meet on a compute unit are nearly equal, and the compute units that get
+// one item more get the shortest ones on top of the smaller sums.
+constexpr int kComputeUnits = 256;
+__device__ __forceinline__ void item_of_workgroup(int wg, int n_items, int n_kv, int& entry, int& kh) {
+  const int rounds = (n_items + kComputeUnits - 1) / kComputeUnits;
+  const int round = wg / kComputeUnits, c = wg - round * kComputeUnits;
+  const bool backwards = ((rounds - 1 - round) & 1) != 0;      // (a backward round is never the partial one)
+  const int item = round * kComputeUnits + (backwards ? kComputeUnits - 1 - c : c);
+  entry = item / n_kv;
+  kh = item - entry * n_kv;
 }
 
 // cache policy of the K/V loads (the builtin's last argument; bit 1 = non-temporal): a step reads its keys and
@@ -209,7 +283,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1
                                                          const bf16_t* __restrict__ k_pages,
                                                          const bf16_t* __restrict__ v_pages,
                                                          const int* __restrict__ block_table, int max_blocks,
-                                                         const int* __restrict__ work, int page_size,
+                                                         const int* __restrict__ work, int n_work, int page_size,
                                                          int n_heads, int n_kv, int steps_per_split,
                                                          int max_splits, int q_row_offset,
                                                          float* __restrict__ partial_o,
@@ -221,10 +295,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1
   constexpr int STAGE = 4 * PART;        // K tile 0, K tile 1, V tile 0, V tile 1
   __shared__ __attribute__((aligned(16))) unsigned char ring[2 * STAGE];
 
-  const int kh = blockIdx.y;
-  // (the grid never exceeds the list's capacity, so the entry may be read before the count is known)
-  const AttnWork wk = *reinterpret_cast<const AttnWork*>(work + 8 + 8 * blockIdx.x);
-  if ((int)blockIdx.x >= work[0]) return;
+  int entry, kh;
+  item_of_workgroup(blockIdx.x, n_work * n_kv, n_kv, entry, kh);
+  // (n_work never exceeds the list's capacity, so the entry may be read before the device's count is known)
+  const AttnWork wk = *reinterpret_cast<const AttnWork*>(work + 8 + 8 * entry);
+  if (entry >= work[0]) return;
   const int srv = wk.srv, split = wk.split, row0 = wk.row0, T = wk.n_tokens, L = wk.ctx;
   const int first_pages[2] = {wk.page0, wk.page1};
   const int lane = threadIdx.x & 63;
@@ -507,36 +582,59 @@ __global__ void attn_combine_kernel(const float* __restrict__ partial_o, const f
 
 }  // namespace
 
-// KV steps (32 keys) per workgroup, and the resulting largest split count, for a batch of n_servers servers
-// with total_steps steps summed over them, max_steps on the longest and query tiles of at most
-// max_block_tokens rows.  Workgroups take equally many steps and share the memory bandwidth, so they finish
-// together when all of them fit the chip at once: the steps per workgroup are chosen for one such round
-// (splits <= total / steps + one ragged tail per server and KV head), which also keeps the partial results
-// few (measured on the 70B shape: 5.9 instead of 6.7 ms per step against two rounds); a floor on the steps
-// per workgroup bounds what the partial results cost on small batches.
+// The most 32-key steps any compute unit is dealt when every server's steps are cut into splits of at most t
+// steps: item_of_workgroup's serpentine over the (server, split, KV head) items in the order of decreasing
+// length, which is the order of the work list.  items: their number.  Splits of 2047 steps and more are not
+// modelled (the histogram lives on the stack): the largest long.
+long attention_busiest_cu(int n_kv, int n_servers, const int* gamma_host, const int* ctx_len_host, long t,
+                          long* items_out) {
+  constexpr long kCus = kComputeUnits, kMaxLen = 2048;
+  long n_of_len[kMaxLen] = {0};
+  long items = 0;
+  for (int i = 0; i < n_servers; ++i) {
+    const long st = ((long)ctx_len_host[i] + gamma_host[i] + 1 + 31) / 32, n = (st + t - 1) / t;
+    const long base = st / n, rem = st - base * n;
+    items += n * n_kv;
+    if (t + 2 > kMaxLen) continue;
+    n_of_len[base + 1] += rem * n_kv;
+    n_of_len[base] += (n - rem) * n_kv;
+  }
+  if (items_out) *items_out = items;
+  if (t + 2 > kMaxLen) return std::numeric_limits<long>::max();
+  const long rounds = (items + kCus - 1) / kCus;
+  long load[kCus] = {0};
+  long pos = 0;
+  for (long len = t + 1; len >= 1; --len)
+    for (long k = 0; k < n_of_len[len]; ++k, ++pos) {
+      const long round = pos / kCus, c = pos - round * kCus;
+      load[((rounds - 1 - round) & 1) ? kCus - 1 - c : c] += len;
+    }
+  return *std::max_element(load, load + kCus);
+}
+
+// KV steps (32 keys) per split, and the resulting largest split count, for a batch of n_servers servers with
+// the given draft lengths and contexts and query tiles of at most max_block_tokens rows.  A server's steps
+// are cut into ceil(steps / steps_per_split) splits of equal length up to one step.  All workgroups of the
+// launch should be resident at once (they share the memory bandwidth; a second round starts with the chip
+// half empty: measured on the 70B shape, 5.9 instead of 6.7 ms per step), which also keeps the partial
+// results few; a floor on the steps per split bounds what the partial results cost on small batches.
 void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, const int* gamma_host,
                     const int* ctx_len_host, int* steps_per_split, int* max_splits) {
   const int tiles = ceil_div(max_block_tokens * group, 32);
   const int waves = tiles < 8 ? (tiles > 0 ? tiles : 1) : 8;
   constexpr int kWavesPerCu = 12;    // by registers (three waves per SIMD)
   const int wgs_per_cu = kWavesPerCu / waves < 5 ? (kWavesPerCu / waves > 0 ? kWavesPerCu / waves : 1) : 5;   // 5 workgroups by LDS
-  constexpr long kCus = 256;
-  const long slots = kCus * wgs_per_cu;
-  auto steps_of = [&](int i) { return (long)(ctx_len_host[i] + gamma_host[i] + 1 + 31) / 32; };
+  const long slots = (long)kComputeUnits * wgs_per_cu;
+  auto steps_of = [&](int i) { return ((long)ctx_len_host[i] + gamma_host[i] + 1 + 31) / 32; };
   long total_steps = 0, max_steps = 1;
   for (int i = 0; i < n_servers; ++i) {
     total_steps += steps_of(i);
     if (steps_of(i) > max_steps) max_steps = steps_of(i);
   }
-  // workgroups of a launch with splits of at most t steps, and the longest split among them
-  auto workgroups = [&](long t, long* longest) {
-    long c = 0, top = 0;
-    for (int i = 0; i < n_servers; ++i) {
-      const long n = (steps_of(i) + t - 1) / t;
-      c += n;
-      if (n > 0 && (steps_of(i) + n - 1) / n > top) top = (steps_of(i) + n - 1) / n;
-    }
-    if (longest) *longest = top;
+  // workgroups of a launch with splits of at most t steps
+  auto workgroups = [&](long t) {
+    long c = 0;
+    for (int i = 0; i < n_servers; ++i) c += (steps_of(i) + t - 1) / t;
     return c * n_kv;
   };
   long lo = (max_steps + 31) / 32;                        // at most 32 splits per server
@@ -544,25 +642,23 @@ void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, co
   if (lo > max_steps) lo = max_steps;
   const long fit = slots - slots / 16;                    // all resident at once, with some slack for placement
   long sps;
-  if (workgroups(max_steps, nullptr) <= fit) {
+  if (workgroups(max_steps) <= fit) {
     // the shortest splits whose workgroups are all resident at once ...
     long a = lo, b = max_steps;
     while (a < b) {
       const long mid = (a + b) / 2;
-      if (workgroups(mid, nullptr) <= fit) b = mid; else a = mid + 1;
+      if (workgroups(mid) <= fit) b = mid; else a = mid + 1;
     }
     sps = a;
-    // ... unless somewhat longer ones load the busiest compute unit less: (workgroups per CU, rounded up) x
-    // (steps of the longest split), e.g. 3 x 22 instead of 4 x 19 steps at the 70B shape with 16 servers
-    auto cu_load = [&](long t) {
-      long longest = 0;
-      const long w = workgroups(t, &longest);
-      return (w + kCus - 1) / kCus * longest;
-    };
-    long best = cu_load(sps);
-    for (long t = sps + 1; t <= sps + sps / 4 && t <= max_steps; ++t) {
-      const long l = cu_load(t);
-      if (l < best) {
+    // ... unless splits up to half longer load the busiest compute unit clearly less (a compute unit's
+    // finishing time follows the steps it is dealt): 3 x 22 instead of 4 x 19 steps at the 70B shape with 16
+    // servers (5.3 against 5.6 ms of attention per step).  Small differences do not pay for the workgroups that
+    // are then missing per compute unit (8 servers at 2048 tokens: 2 x 9 steps on 512 workgroups took 17.1 us
+    // per layer, 3 x 6 on 704 take 15.1), hence the margin of 8 %.
+    long best = attention_busiest_cu(n_kv, n_servers, gamma_host, ctx_len_host, sps, nullptr);
+    for (long t = sps + 1; t <= sps + sps / 2 && t <= max_steps; ++t) {
+      const long l = attention_busiest_cu(n_kv, n_servers, gamma_host, ctx_len_host, t, nullptr);
+      if (l * 100 < best * 92) {
         best = l;
         sps = t;
       }
@@ -590,12 +686,12 @@ static gs_status launch_mfma_g(const bf16_t* q, const bf16_t* k_pages, const bf1
                                int n_heads, int n_kv, int max_block_tokens, int steps_per_split, int max_splits,
                                float* po, float* pml, hipStream_t stream) {
   const int tiles = ceil_div(max_block_tokens * G, 32);
-  dim3 grid(n_work, n_kv);
+  dim3 grid((unsigned)n_work * (unsigned)n_kv);      // one workgroup per (entry, KV head) item, see item_of_workgroup
   for (int t0 = 0; t0 < tiles; t0 += 8) {      // at most 8 query tiles (waves) per workgroup
     const int waves = tiles - t0 < 8 ? tiles - t0 : 8;
 #define GS_RING(NW_)                                                                                              \
   attn_kernel<HD, G, NW_><<<grid, 64 * NW_, 0, stream>>>(q, k_pages, v_pages, block_table, max_blocks, work,      \
-                                                         page_size, n_heads, n_kv, steps_per_split, max_splits,   \
+                                                         n_work, page_size, n_heads, n_kv, steps_per_split, max_splits,   \
                                                          t0 * 32, po, pml)
     switch (waves) {
       case 1: GS_RING(1); break;

@@ -31,6 +31,8 @@ gs_status launch_rope_append(int dtype, const float* qkv, int n_splits, int n_ro
 gs_status launch_swiglu(int dtype, const float* gu, int n_splits, int n_rows, int F, void* act, hipStream_t stream);
 void attention_plan(int n_kv, int group, int max_block_tokens, int n_servers, const int* gamma_host,
                     const int* ctx_len_host, int* steps_per_split, int* max_splits);
+long attention_busiest_cu(int n_kv, int n_servers, const int* gamma_host, const int* ctx_len_host, long t,
+                          long* items_out);
 size_t attention_workspace_floats(int n_rows, int n_heads, int hd, int max_splits);
 gs_status launch_attention(int dtype, const void* q, const void* k_pages, const void* v_pages,
                            const int* block_table, int max_blocks, const int* cu_rows, const int* ctx_len,
@@ -536,6 +538,27 @@ extern "C" gs_status gs_check_batch(const gs_ctx* ctx, const gs_kv_cache* kv, co
     case kBadToken: return gs::fail(GS_EINVAL, "tokens[%d] = %d of server %d is outside the vocabulary", err[2], err[3], err[1]);
     default: return gs::fail(GS_EINVAL, "block_table[%d][%d] = %d is not a page of the cache", err[1], err[2], err[3]);
   }
+}
+
+extern "C" gs_status gs_plan_attention(int n_kv_heads, int group, int n_servers, const int* gamma_host,
+                                       const int* ctx_len_host, int* steps_per_split, long* n_workgroups,
+                                       long* busiest_cu_steps) {
+  if (n_kv_heads <= 0 || group <= 0 || n_servers <= 0 || !gamma_host || !ctx_len_host || !steps_per_split)
+    return gs::fail(GS_EINVAL, "gs_plan_attention: bad argument");
+  int max_t = 0;
+  for (int i = 0; i < n_servers; ++i) {
+    if (gamma_host[i] < 0 || ctx_len_host[i] < 0)
+      return gs::fail(GS_EINVAL, "server %d: gamma = %d, ctx_len = %d", i, gamma_host[i], ctx_len_host[i]);
+    max_t = std::max(max_t, gamma_host[i] + 1);
+  }
+  int sps = 1, splits = 1;
+  gs::attention_plan(n_kv_heads, group, max_t, n_servers, gamma_host, ctx_len_host, &sps, &splits);
+  long items = 0;
+  const long busiest = gs::attention_busiest_cu(n_kv_heads, n_servers, gamma_host, ctx_len_host, sps, &items);
+  *steps_per_split = sps;
+  if (n_workgroups) *n_workgroups = items;
+  if (busiest_cu_steps) *busiest_cu_steps = busiest;
+  return GS_OK;
 }
 
 extern "C" gs_status gs_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {

@@ -125,3 +125,52 @@ def test_baseline_allocation_policies_of_the_loop_equal_the_oracle():
         got = cl.random_split(C, n, u)
         np.testing.assert_array_equal(got, ol.random_allocation(C, n, u))
         assert got.sum() == C
+
+
+def _serpentine_busiest(steps, t, n_kv):
+    """Brute force of what the planner models: split lengths sorted longest first, dealt to 256 compute units in
+    rounds that alternate direction counted from the last (forward) round."""
+    lens = []
+    for st in steps:
+        n = -(-st // t)
+        base, rem = divmod(st, n)
+        lens += [base + 1] * (rem * n_kv) + [base] * ((n - rem) * n_kv)
+    lens.sort(reverse=True)
+    rounds = -(-len(lens) // 256)
+    load = [0] * 256
+    for p, l in enumerate(lens):
+        r, c = divmod(p, 256)
+        load[255 - c if (rounds - 1 - r) & 1 else c] += l
+    return len(lens), max(load)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_attention_plan_invariants_on_random_batches(seed):
+    rng = np.random.default_rng(7000 + seed)
+    n = int(rng.choice([1, 3, 8, 32, 200, 900]))
+    n_kv = int(rng.choice([1, 2, 8]))
+    group = int(rng.choice([1, 4, 8]))
+    gamma = rng.integers(0, int(rng.choice([2, 9, 17])), n)
+    ctx = rng.integers(0, int(rng.choice([50, 3000, 40000])), n)
+    sps, items, busiest = gsb.gs_plan_attention(n_kv, group, gamma, ctx)
+    steps = ((ctx + gamma + 1 + 31) // 32).tolist()
+    assert 1 <= sps <= max(steps)
+    assert sps >= min(6, max(steps))                      # floor on the split length
+    assert max(-(-s // sps) for s in steps) <= 32         # at most 32 splits per server
+    want_items, want_busiest = _serpentine_busiest(steps, sps, n_kv)
+    assert items == want_items == sum(-(-s // sps) for s in steps) * n_kv
+    assert busiest == want_busiest
+    assert busiest >= -(-sum(steps) * n_kv // 256)        # no compute unit below the mean is the busiest
+
+
+def test_attention_plan_of_the_measured_workloads():
+    # uniform contexts: 8 servers at 2048 tokens keep the shortest splits (6 steps, 704 workgroups); 16 servers at
+    # 4096 tokens with 8 KV heads take 6 splits of 22 steps (3 per compute unit) instead of 7 of 19
+    assert gsb.gs_plan_attention(8, 4, np.full(8, 6), np.full(8, 2048)) == (6, 704, 18)
+    sps, items, busiest = gsb.gs_plan_attention(8, 8, np.full(16, 8), np.full(16, 4096))   # 72 query rows: 3 waves
+    assert (sps, items) == (22, 768) and busiest <= 66
+    # one server: all of the chip's workgroups come from its own splits
+    sps, items, _ = gsb.gs_plan_attention(8, 4, [4], [131072])
+    assert items == 8 * -(-4097 // sps) and items <= 32 * 8
+    with pytest.raises(gsb.GsError):
+        gsb.gs_plan_attention(8, 4, [-1], [10])
