@@ -13,7 +13,7 @@ _capture_manager = None
 
 def progress(msg):
     """A progress line of a long test that reaches the terminal even while pytest captures output (a run that
-    prints nothing for minutes is taken for a hung one), and the file gpurun_out/test_progress.log if that
+    prints nothing for minutes is taken for a hung one), and a log file in the run's output folder if that
     folder exists.  Called by the work itself (a layer checked, a stage uploaded), never from a timer."""
     line = f"[progress] {msg}"
     if _capture_manager is not None:
