@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 # profiles/hbm_traffic_counters.md (121.79 MB fetched + 5.34 MB written, scaled by the copy-kernel factors
 # given there).  Valid only for the kernel source it was taken with: reported as null once gemm.hip changes.
 GEMM_TRAFFIC = {"gemm_hip_sha256": "def0d05baaf8661cf2cf8a42697f8573210332859236e6e404e9fda1c04617e1",
-                "bytes_per_launch": 127131062}
+                "bytes_per_launch": 127128302}
 
 
 def measured_traffic():
